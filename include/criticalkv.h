@@ -1,0 +1,161 @@
+/*
+ * criticalkv.h - C ABI of the per-layer KV-cache selection pass on AMD MI355X (gfx950).
+ *
+ * The pass is the prefill-time "score -> select -> compact" step of
+ * perturbation-constrained KV-cache eviction:
+ *   score   : observation-window attention (Algorithm 2, lines 2-4) and the
+ *             per-entry L1 magnitude of the value projected through its head's
+ *             slice of W^O (Theorem 3.3; Algorithm 1, lines 2-3)
+ *   select  : budget split b' = b*alpha, b'' = b - b' and the two Top-k stages
+ *             (Algorithm 1, lines 4-9)
+ *   compact : the selected K/V rows gathered into the new cache
+ *             (Algorithm 1, line 10; Definition 3.1)
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers (HIP global memory) unless a
+ *     parameter says "host".  Tensors are row-major with the last dimension
+ *     contiguous.  The descriptor is a host struct and is read during the call.
+ *   - Ownership: the caller owns every buffer.  The library allocates nothing,
+ *     frees nothing and keeps no pointer after a call returns; temporary device
+ *     memory is the caller's `workspace` (size from criticalkv_workspace_bytes,
+ *     256-byte aligned).  Inputs are never modified.  Outputs must not alias
+ *     inputs or the workspace.
+ *   - Execution: work is enqueued on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and the call returns without waiting.
+ *     score -> select -> compact on one stream need no host synchronisation.
+ *     Two calls that share a workspace must be ordered on one stream.
+ *   - Errors: 0 on success, a negative CKV_E_* code otherwise.  Arguments are
+ *     validated before any HIP call, so CKV_E_INVALID_ARG / CKV_E_UNSUPPORTED /
+ *     CKV_E_WORKSPACE are returned without touching a device.  No exception
+ *     crosses this boundary.  Non-finite input values give undefined scores.
+ */
+#ifndef CRITICALKV_H
+#define CRITICALKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CKV_API __attribute__((visibility("default")))
+
+/* error codes */
+#define CKV_OK 0
+#define CKV_E_INVALID_ARG (-1) /* null pointer, shape or parameter out of range            */
+#define CKV_E_UNSUPPORTED (-2) /* valid request this build has no kernel for               */
+#define CKV_E_WORKSPACE (-3)   /* workspace missing, misaligned or too small               */
+#define CKV_E_HIP (-4)         /* a HIP launch failed (hipGetLastError was not hipSuccess) */
+
+/* ckv_layer_desc.dtype: element type of q_win, k, v, w_o and of k_out, v_out */
+#define CKV_BF16 0
+#define CKV_F32 1
+
+/* ckv_layer_desc.norm: norm applied to each row of V W^O (the paper's results use L1) */
+#define CKV_NORM_L1 1
+
+/* ckv_layer_desc.window_reduce: how the W window rows are merged (Algorithm 2 line 3 takes the mean) */
+#define CKV_MEAN 0
+#define CKV_SUM 1
+
+/* ckv_layer_desc.flags */
+#define CKV_WO_OUT_IN 1u /* w_o is stored [d_model, H*d_h] (the layout of a linear layer's weight:
+                            output feature major); without it w_o is [H*d_h, d_model], head h = rows
+                            h*d_h .. (h+1)*d_h-1, i.e. the paper's d_h x d slice per head (Section 3.1) */
+#define CKV_NO_MFMA 2u   /* run the plain vector-ALU kernels even where a matrix-core kernel exists
+                            (same results up to fp32 rounding order; for validation)               */
+
+/*
+ * One attention layer.  Notation of the paper: n cached entries per head, window of n' = `window`
+ * queries, per-head output-projection slice W^O of shape d_h x d.  Grouped-query attention:
+ * query head h reads kv head h / (n_q_heads / n_kv_heads).
+ */
+typedef struct ckv_layer_desc {
+    int32_t batch;         /* >= 1                                                            */
+    int32_t n_q_heads;     /* H, multiple of n_kv_heads                                       */
+    int32_t n_kv_heads;    /* Hkv                                                             */
+    int32_t head_dim;      /* d_h: 64 or 128                                                  */
+    int32_t d_model;       /* d: columns of W^O, multiple of 32                               */
+    int32_t n_ctx;         /* n >= 1 cached entries per head                                  */
+    int32_t window;        /* n' = W observation-window queries, 1 <= W <= n                  */
+    int32_t pool_kernel;   /* odd max-pool width over the token axis, 1 = no pooling          */
+    int32_t dtype;         /* CKV_BF16 or CKV_F32                                             */
+    int32_t norm;          /* CKV_NORM_L1                                                     */
+    int32_t window_reduce; /* CKV_MEAN or CKV_SUM                                             */
+    uint32_t flags;        /* CKV_WO_OUT_IN | CKV_NO_MFMA                                     */
+    float softmax_scale;   /* logit scale; 0 selects 1/sqrt(head_dim) (eq. 2)                 */
+    float eps;             /* added to the pooled score before the product (paper: 1e-4)      */
+    int64_t k_stride[3];   /* element strides of k for (batch, kv head, token); all 0 =       */
+    int64_t v_stride[3];   /*   contiguous [batch, Hkv, n, d_h].  The last dim has stride 1.  */
+} ckv_layer_desc;
+
+/*
+ * Bytes of workspace that criticalkv_score and criticalkv_select need for this layer
+ * (the larger of the two; compact needs none).  Returns 0 if the descriptor is invalid.
+ * Host-only computation.
+ */
+CKV_API size_t criticalkv_workspace_bytes(const ckv_layer_desc *desc, int32_t max_budget);
+
+/*
+ * Scores of every cached entry (Algorithm 2 lines 2-4; Algorithm 1 lines 2-3).
+ *
+ * Per batch item bi, query head h with kv head g = h / G, G = H / Hkv:
+ *   p_{w,.}   = softmax_i(scale * q_win[bi,h,w,:] . k[bi,g,i,:])   over all n keys, no mask
+ *   a^h_i     = mean_w p_{w,i}          (sum_w with CKV_SUM)
+ *   abar^h_i  = max{ a^h_j : |j - i| <= pool_kernel/2, 0 <= j < n }
+ *   N^h_i     = sum_c | sum_t v[bi,g,i,t] * W^O[h*d_h + t, c] |
+ * and, per kv head (group means; with G = 1 exactly the paper's A and (A + eps) * ||V W^O||_1):
+ *   attn[bi,g,i] = (1/G) sum_{h in g} abar^h_i
+ *   crit[bi,g,i] = (1/G) sum_{h in g} (abar^h_i + eps) * N^h_i
+ *
+ * in : q_win [batch, H, W, d_h]   the last W query states of the prompt
+ *      k, v  [batch, Hkv, n, d_h] (or strided per the descriptor)
+ *      w_o   [H*d_h, d_model]     (or [d_model, H*d_h] with CKV_WO_OUT_IN)
+ * out: attn, crit [batch, Hkv, n] float32
+ *      vnorm_opt  [batch, H, n]   float32, N^h_i; may be NULL
+ * bf16 inputs are multiplied exactly and accumulated in float32.
+ */
+CKV_API int criticalkv_score(const ckv_layer_desc *desc, const void *q_win, const void *k, const void *v,
+                             const void *w_o, float *attn, float *crit, float *vnorm_opt, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Two-stage selection per (batch item, kv head) (Algorithm 1 lines 4-9).
+ *
+ *   B   = clamp(budget[bi,g], 0, min(n, max_budget))
+ *   b'  = floor(alpha * B) (in double), b'' = B - b'
+ *   S1  = the b' entries with the largest attn
+ *   S2  = the b'' entries with the largest crit among entries not in S1
+ * Equal keys: the lower token index is taken first.  Keys are compared as IEEE floats
+ * (-0 equals +0); NaN keys give an undefined selection.
+ *
+ * in : attn, crit [batch, Hkv, n] float32 (normally criticalkv_score's outputs)
+ *      budget     [batch, Hkv]    int32, DEVICE memory
+ *      alpha      in [0, 1]; 1 = attention-only Top-B (Algorithm 2's regular selection)
+ * out: idx   [batch, Hkv, max_budget] int32: S1 u S2 in ascending token order, tail filled with -1
+ *      count [batch, Hkv]             int32: B
+ */
+CKV_API int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float *crit,
+                              const int32_t *budget, float alpha, int32_t max_budget, int32_t *idx,
+                              int32_t *count, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Compacted cache (Algorithm 1 line 10):  k_out[bi,g,j,:] = k[bi,g,idx[bi,g,j],:] for j < count[bi,g],
+ * likewise v_out.  Rows j >= count[bi,g] are left untouched.  Bit-exact copies in the input dtype.
+ *
+ * in : k, v [batch, Hkv, n, d_h] (or strided per the descriptor); idx, count from criticalkv_select
+ * out: k_out, v_out [batch, Hkv, max_budget, d_h] contiguous
+ * An index outside [0, n) is skipped (its output row is left untouched).
+ */
+CKV_API int criticalkv_compact(const ckv_layer_desc *desc, const void *k, const void *v, const int32_t *idx,
+                               const int32_t *count, int32_t max_budget, void *k_out, void *v_out,
+                               void *hip_stream);
+
+/* Static, NUL-terminated description of an error code. */
+CKV_API const char *criticalkv_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CRITICALKV_H */

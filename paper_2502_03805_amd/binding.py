@@ -1,0 +1,124 @@
+"""Thin ctypes binding of libcriticalkv.so.
+
+Argument marshalling only: tensors are PyTorch-ROCm device buffers, every step of the
+pass runs inside the library's gfx950 kernels.  There is no CPU fallback: if the shared
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG, "libcriticalkv.so")
+
+CKV_BF16, CKV_F32 = 0, 1
+CKV_NORM_L1 = 1
+CKV_MEAN, CKV_SUM = 0, 1
+CKV_WO_OUT_IN, CKV_NO_MFMA = 1, 2
+CKV_OK, CKV_E_INVALID_ARG, CKV_E_UNSUPPORTED, CKV_E_WORKSPACE, CKV_E_HIP = 0, -1, -2, -3, -4
+
+EXPORTS = ("criticalkv_workspace_bytes", "criticalkv_score", "criticalkv_select", "criticalkv_compact",
+           "criticalkv_strerror")
+
+
+class LayerDesc(ctypes.Structure):
+    """Mirror of ckv_layer_desc in include/criticalkv.h."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("d_model", ctypes.c_int32), ("n_ctx", ctypes.c_int32),
+        ("window", ctypes.c_int32), ("pool_kernel", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("norm", ctypes.c_int32), ("window_reduce", ctypes.c_int32), ("flags", ctypes.c_uint32),
+        ("softmax_scale", ctypes.c_float), ("eps", ctypes.c_float),
+        ("k_stride", ctypes.c_int64 * 3), ("v_stride", ctypes.c_int64 * 3),
+    ]
+
+
+class CriticalKVError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} (code {code})")
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the built library.  Raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2502_03805_amd.build` "
+                              "(or __graft_entry__.build()) first")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
+        dp = ctypes.POINTER(LayerDesc)
+        lib.criticalkv_workspace_bytes.restype = ctypes.c_size_t
+        lib.criticalkv_workspace_bytes.argtypes = [dp, i32]
+        lib.criticalkv_score.restype = ctypes.c_int
+        lib.criticalkv_score.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.criticalkv_select.restype = ctypes.c_int
+        lib.criticalkv_select.argtypes = [dp, vp, vp, vp, f32, i32, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.criticalkv_compact.restype = ctypes.c_int
+        lib.criticalkv_compact.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp]
+        lib.criticalkv_strerror.restype = ctypes.c_char_p
+        lib.criticalkv_strerror.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return load().criticalkv_strerror(int(code)).decode()
+
+
+def make_desc(*, batch, n_q_heads, n_kv_heads, head_dim, d_model, n_ctx, window, pool_kernel, dtype,
+              norm=CKV_NORM_L1, window_reduce=CKV_MEAN, flags=0, softmax_scale=0.0, eps=1e-4,
+              k_stride=(0, 0, 0), v_stride=(0, 0, 0)) -> LayerDesc:
+    d = LayerDesc()
+    d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim, d.d_model = batch, n_q_heads, n_kv_heads, head_dim, d_model
+    d.n_ctx, d.window, d.pool_kernel, d.dtype, d.norm = n_ctx, window, pool_kernel, dtype, norm
+    d.window_reduce, d.flags, d.softmax_scale, d.eps = window_reduce, flags, softmax_scale, eps
+    d.k_stride = (ctypes.c_int64 * 3)(*k_stride)
+    d.v_stride = (ctypes.c_int64 * 3)(*v_stride)
+    return d
+
+
+def workspace_bytes(desc: LayerDesc, max_budget: int) -> int:
+    return int(load().criticalkv_workspace_bytes(ctypes.byref(desc), int(max_budget)))
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def criticalkv_score(desc: LayerDesc, q_win, k, v, w_o, attn, crit, vnorm=None, *, workspace, stream=None) -> None:
+    rc = load().criticalkv_score(ctypes.byref(desc), _ptr(q_win), _ptr(k), _ptr(v), _ptr(w_o), _ptr(attn), _ptr(crit),
+                                 _ptr(vnorm), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _stream(stream))
+    if rc != CKV_OK:
+        raise CriticalKVError(rc, "criticalkv_score")
+
+
+def criticalkv_select(desc: LayerDesc, attn, crit, budget, alpha: float, max_budget: int, idx, count, *, workspace,
+                      stream=None) -> None:
+    rc = load().criticalkv_select(ctypes.byref(desc), _ptr(attn), _ptr(crit), _ptr(budget), float(alpha),
+                                  int(max_budget), _ptr(idx), _ptr(count), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != CKV_OK:
+        raise CriticalKVError(rc, "criticalkv_select")
+
+
+def criticalkv_compact(desc: LayerDesc, k, v, idx, count, max_budget: int, k_out, v_out, *, stream=None) -> None:
+    rc = load().criticalkv_compact(ctypes.byref(desc), _ptr(k), _ptr(v), _ptr(idx), _ptr(count), int(max_budget),
+                                   _ptr(k_out), _ptr(v_out), _stream(stream))
+    if rc != CKV_OK:
+        raise CriticalKVError(rc, "criticalkv_compact")

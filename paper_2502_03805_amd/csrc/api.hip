@@ -1,0 +1,178 @@
+// Host side of the C ABI: argument validation, workspace carving, kernel dispatch.
+// Nothing here computes any part of the pass; every step runs in the gfx950 kernels.
+#include <math.h>
+
+#include "common.hpp"
+
+namespace ckv {
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static size_t elem_size(int dtype) { return dtype == CKV_F32 ? 4 : 2; }
+
+// Validates the descriptor and resolves defaults.  No HIP call.
+static int resolve(const ckv_layer_desc *desc, Dims *out)
+{
+    if (!desc) return CKV_E_INVALID_ARG;
+    const ckv_layer_desc &c = *desc;
+    if (c.batch < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.n_ctx < 1 || c.d_model < 1) return CKV_E_INVALID_ARG;
+    if (c.n_q_heads % c.n_kv_heads) return CKV_E_INVALID_ARG;
+    if (c.window < 1 || c.window > c.n_ctx) return CKV_E_INVALID_ARG;
+    if (c.pool_kernel < 1 || (c.pool_kernel % 2) == 0) return CKV_E_INVALID_ARG;
+    if (c.dtype != CKV_BF16 && c.dtype != CKV_F32) return CKV_E_INVALID_ARG;
+    if (c.window_reduce != CKV_MEAN && c.window_reduce != CKV_SUM) return CKV_E_INVALID_ARG;
+    if (c.flags & ~(CKV_WO_OUT_IN | CKV_NO_MFMA)) return CKV_E_INVALID_ARG;
+    if (!(c.softmax_scale >= 0.0f) || !isfinite(c.softmax_scale)) return CKV_E_INVALID_ARG;
+    if (!(c.eps >= 0.0f) || !isfinite(c.eps)) return CKV_E_INVALID_ARG;
+    if (c.head_dim != 64 && c.head_dim != 128) return CKV_E_UNSUPPORTED;
+    if (c.d_model % 32) return CKV_E_UNSUPPORTED;
+    if (c.norm != CKV_NORM_L1) return CKV_E_UNSUPPORTED;
+    if (c.pool_kernel > 63) return CKV_E_UNSUPPORTED;
+    if ((int64_t)c.window * c.head_dim > 12288) return CKV_E_UNSUPPORTED; // window queries are staged in LDS
+    // index arithmetic inside the kernels is 64-bit for tensors and 32-bit for per-head token indices
+    if ((int64_t)c.batch * c.n_q_heads * c.window > (int64_t)1 << 24) return CKV_E_UNSUPPORTED;
+    if ((int64_t)c.batch * c.n_q_heads > 65535) return CKV_E_UNSUPPORTED;
+
+    Dims d;
+    d.batch = c.batch; d.H = c.n_q_heads; d.Hkv = c.n_kv_heads; d.G = d.H / d.Hkv;
+    d.dh = c.head_dim; d.dm = c.d_model; d.n = c.n_ctx; d.W = c.window; d.pool_k = c.pool_kernel;
+    d.window_sum = c.window_reduce == CKV_SUM;
+    d.scale = c.softmax_scale > 0.0f ? c.softmax_scale : 1.0f / sqrtf((float)c.head_dim);
+    d.eps = c.eps;
+    const int64_t contiguous[3] = {(int64_t)d.Hkv * d.n * d.dh, (int64_t)d.n * d.dh, (int64_t)d.dh};
+    const int64_t *src[2] = {c.k_stride, c.v_stride};
+    int64_t *dst[2] = {d.ks, d.vs};
+    for (int t = 0; t < 2; ++t) {
+        const bool all_zero = src[t][0] == 0 && src[t][1] == 0 && src[t][2] == 0;
+        for (int j = 0; j < 3; ++j) dst[t][j] = all_zero ? contiguous[j] : src[t][j];
+        if (dst[t][2] < d.dh || dst[t][0] < 0 || dst[t][1] < 0) return CKV_E_INVALID_ARG;
+        // vector loads of 16 bytes need rows that start on a 16-byte boundary
+        const int64_t per16 = 16 / (int64_t)elem_size(c.dtype);
+        if (dst[t][0] % per16 || dst[t][1] % per16 || dst[t][2] % per16) return CKV_E_UNSUPPORTED;
+    }
+    *out = d;
+    return CKV_OK;
+}
+
+Workspace carve_workspace(const Dims &d, int dtype, bool need_wt)
+{
+    Workspace w;
+    size_t off = 0;
+    const size_t per_head = (size_t)d.batch * d.H * d.n;
+    w.max_chunks = (d.n + ATTN_MIN_CHUNK - 1) / ATTN_MIN_CHUNK;
+    w.a_raw = off; off = align256(off + per_head * 4);
+    w.vnorm = off; off = align256(off + per_head * 4);
+    w.stats_part = off; off = align256(off + (size_t)d.batch * d.H * d.W * w.max_chunks * 2 * 4);
+    w.stats = off; off = align256(off + (size_t)d.batch * d.H * d.W * 2 * 4);
+    w.w_t = off; if (need_wt) off = align256(off + (size_t)d.H * d.dh * d.dm * elem_size(dtype));
+    w.sel_keys = off; off = align256(off + (size_t)d.batch * d.Hkv * d.n * 4);
+    w.total = off;
+    return w;
+}
+
+static bool mfma_allowed(const ckv_layer_desc *desc)
+{
+    return desc->dtype == CKV_BF16 && !(desc->flags & CKV_NO_MFMA);
+}
+
+} // namespace ckv
+
+using namespace ckv;
+
+extern "C" {
+
+size_t criticalkv_workspace_bytes(const ckv_layer_desc *desc, int32_t max_budget)
+{
+    Dims d;
+    if (resolve(desc, &d) != CKV_OK || max_budget < 0) return 0;
+    // sized for either w_o layout so that one allocation serves both
+    return carve_workspace(d, desc->dtype, true).total;
+}
+
+int criticalkv_score(const ckv_layer_desc *desc, const void *q_win, const void *k, const void *v, const void *w_o,
+                     float *attn, float *crit, float *vnorm_opt, void *workspace, size_t workspace_bytes,
+                     void *hip_stream)
+{
+    Dims d;
+    int rc = resolve(desc, &d);
+    if (rc != CKV_OK) return rc;
+    if (!q_win || !k || !v || !w_o || !attn || !crit) return CKV_E_INVALID_ARG;
+    const bool need_wt = !(desc->flags & CKV_WO_OUT_IN);
+    const Workspace ws = carve_workspace(d, desc->dtype, need_wt);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *base = (char *)workspace;
+    float *a_raw = (float *)(base + ws.a_raw);
+    float *vnorm = vnorm_opt ? vnorm_opt : (float *)(base + ws.vnorm);
+    float *part = (float *)(base + ws.stats_part);
+    float *stats = (float *)(base + ws.stats);
+    const void *w_t = w_o;
+    hipError_t e;
+    if (need_wt) {
+        e = launch_transpose_wo(d, desc->dtype, w_o, base + ws.w_t, s);
+        if (e != hipSuccess) return CKV_E_HIP;
+        w_t = base + ws.w_t;
+    }
+    const bool mfma_a = mfma_allowed(desc) && attn_mfma_supported(d);
+    const bool mfma_v = mfma_allowed(desc) && vproj_mfma_supported(d);
+    const int chunks = mfma_a ? mfma_attn_chunks(d) : generic_attn_chunks(d);
+    if (chunks > ws.max_chunks) return CKV_E_WORKSPACE;
+
+    e = mfma_a ? launch_attn_stats_mfma(d, q_win, k, part, chunks, s)
+               : launch_attn_stats_generic(d, desc->dtype, q_win, k, part, chunks, s);
+    if (e != hipSuccess) return CKV_E_HIP;
+    e = launch_attn_stats_reduce(d, part, chunks, stats, s);
+    if (e != hipSuccess) return CKV_E_HIP;
+    e = mfma_a ? launch_attn_colsum_mfma(d, q_win, k, stats, a_raw, s)
+               : launch_attn_colsum_generic(d, desc->dtype, q_win, k, stats, a_raw, s);
+    if (e != hipSuccess) return CKV_E_HIP;
+    e = mfma_v ? launch_vproj_mfma(d, v, w_t, vnorm, s) : launch_vproj_generic(d, desc->dtype, v, w_t, vnorm, s);
+    if (e != hipSuccess) return CKV_E_HIP;
+    e = launch_combine(d, a_raw, vnorm, attn, crit, s);
+    if (e != hipSuccess) return CKV_E_HIP;
+    return CKV_OK;
+}
+
+int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float *crit, const int32_t *budget,
+                      float alpha, int32_t max_budget, int32_t *idx, int32_t *count, void *workspace,
+                      size_t workspace_bytes, void *hip_stream)
+{
+    Dims d;
+    int rc = resolve(desc, &d);
+    if (rc != CKV_OK) return rc;
+    if (!attn || !crit || !budget || !idx || !count) return CKV_E_INVALID_ARG;
+    if (!(alpha >= 0.0f) || !(alpha <= 1.0f)) return CKV_E_INVALID_ARG;
+    if (max_budget < 1 || max_budget > d.n) return CKV_E_INVALID_ARG;
+    const Workspace ws = carve_workspace(d, desc->dtype, false);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
+    uint32_t *keys2 = (uint32_t *)((char *)workspace + ws.sel_keys);
+    hipError_t e = launch_select(d, attn, crit, budget, alpha, max_budget, idx, count, keys2, (hipStream_t)hip_stream);
+    return e == hipSuccess ? CKV_OK : CKV_E_HIP;
+}
+
+int criticalkv_compact(const ckv_layer_desc *desc, const void *k, const void *v, const int32_t *idx,
+                       const int32_t *count, int32_t max_budget, void *k_out, void *v_out, void *hip_stream)
+{
+    Dims d;
+    int rc = resolve(desc, &d);
+    if (rc != CKV_OK) return rc;
+    if (!k || !v || !idx || !count || !k_out || !v_out) return CKV_E_INVALID_ARG;
+    if (max_budget < 1 || max_budget > d.n) return CKV_E_INVALID_ARG;
+    hipError_t e = launch_compact(d, desc->dtype, k, v, idx, count, max_budget, k_out, v_out, (hipStream_t)hip_stream);
+    return e == hipSuccess ? CKV_OK : CKV_E_HIP;
+}
+
+const char *criticalkv_strerror(int code)
+{
+    switch (code) {
+    case CKV_OK: return "success";
+    case CKV_E_INVALID_ARG: return "invalid argument (null pointer, shape or parameter out of range)";
+    case CKV_E_UNSUPPORTED: return "unsupported configuration (head_dim, d_model, norm, strides or sizes)";
+    case CKV_E_WORKSPACE: return "workspace missing, not 256-byte aligned or too small";
+    case CKV_E_HIP: return "a HIP kernel launch failed";
+    default: return "unknown error code";
+    }
+}
+
+} // extern "C"

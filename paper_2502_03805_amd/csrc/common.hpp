@@ -1,0 +1,74 @@
+// Internal declarations shared by the host dispatch and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "criticalkv.h"
+
+namespace ckv {
+
+// bf16 storage type: raw 16 bits; conversion to float is a shift (exact).
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return bf16_to_f32(x); }
+
+// Problem sizes resolved from the descriptor (strides filled in).
+struct Dims {
+    int batch, H, Hkv, G, dh, dm, n, W, pool_k;
+    int window_sum;
+    float scale, eps;
+    int64_t ks[3], vs[3];
+};
+
+// Workspace carving for criticalkv_score / criticalkv_select (byte offsets, 256-aligned).
+struct Workspace {
+    size_t a_raw;      // [batch, H, n] f32: window score per query head before pooling
+    size_t vnorm;      // [batch, H, n] f32: projected-value norm (when the caller passes none)
+    size_t stats_part; // [batch, H, W, chunks, 2] f32: per-chunk (max, sum of exp)
+    size_t stats;      // [batch, H, W, 2] f32: per-row (max + log sum, unused)
+    size_t w_t;        // [d_model, H*dh] copy of W_O in output-major layout (when given canonical)
+    size_t sel_keys;   // [batch*Hkv, n] u32: stage-2 keys with stage-1 entries marked
+    size_t total;
+    int max_chunks;    // capacity of stats_part per window row
+};
+
+constexpr int ATTN_MIN_CHUNK = 256; // fewest keys any attention kernel gives one workgroup (sizes stats_part)
+int generic_attn_chunks(const Dims &d);
+int mfma_attn_chunks(const Dims &d);
+bool attn_mfma_supported(const Dims &d);  // shapes the matrix-core attention kernels cover
+bool vproj_mfma_supported(const Dims &d); // shapes the matrix-core projection kernel covers
+
+Workspace carve_workspace(const Dims &d, int dtype, bool need_wt);
+
+// ---- kernel launchers (each returns hipGetLastError after its launches) -------------------------
+// window attention, pass 1: per (row, key chunk) running max and sum of exp
+hipError_t launch_attn_stats_generic(const Dims &d, int dtype, const void *q, const void *k, float *part,
+                                     int chunks, hipStream_t s);
+// reduce chunk partials to one (max, 1/sum) pair per window row
+hipError_t launch_attn_stats_reduce(const Dims &d, const float *part, int chunks, float *stats, hipStream_t s);
+// window attention, pass 2: a_raw[b,h,i] = reduce_w exp(s - max_w) / sum_w
+hipError_t launch_attn_colsum_generic(const Dims &d, int dtype, const void *q, const void *k, const float *stats,
+                                      float *a_raw, hipStream_t s);
+hipError_t launch_attn_stats_mfma(const Dims &d, const void *q, const void *k, float *part, int chunks,
+                                  hipStream_t s);
+hipError_t launch_attn_colsum_mfma(const Dims &d, const void *q, const void *k, const float *stats, float *a_raw,
+                                   hipStream_t s);
+// projected-value L1 norm; w_t is [d_model, H*dh]
+hipError_t launch_vproj_generic(const Dims &d, int dtype, const void *v, const void *w_t, float *vnorm,
+                                hipStream_t s);
+hipError_t launch_vproj_mfma(const Dims &d, const void *v, const void *w_t, float *vnorm, hipStream_t s);
+// [H*dh, d_model] -> [d_model, H*dh]
+hipError_t launch_transpose_wo(const Dims &d, int dtype, const void *w_o, void *w_t, hipStream_t s);
+// pool + eps + product + group mean
+hipError_t launch_combine(const Dims &d, const float *a_raw, const float *vnorm, float *attn, float *crit,
+                          hipStream_t s);
+hipError_t launch_select(const Dims &d, const float *attn, const float *crit, const int32_t *budget, float alpha,
+                         int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2, hipStream_t s);
+hipError_t launch_compact(const Dims &d, int dtype, const void *k, const void *v, const int32_t *idx,
+                          const int32_t *count, int max_budget, void *k_out, void *v_out, hipStream_t s);
+
+} // namespace ckv

@@ -1,0 +1,132 @@
+"""Shared test plumbing: device marshalling for the GPU path and the parity rules.
+
+The comparison rules are the acceptance criteria of the build:
+  * scores within 2e-3 relative of the float64 oracle (bf16 inputs, fp32 accumulation);
+  * selected index sets identical, except for swaps between entries whose oracle key lies
+    within 2e-3 relative of the stage threshold; every swap is counted.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import numpy as np
+
+REL_TOL = 2e-3
+
+
+def cfg_desc(P, cfg, *, flags=0, window_reduce=None, softmax_scale=0.0, **over):
+    kw = dict(batch=cfg.batch, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+              d_model=cfg.d_model, n_ctx=cfg.n_ctx, window=cfg.window, pool_kernel=cfg.pool_kernel,
+              dtype=P.CKV_BF16 if cfg.dtype == "bf16" else P.CKV_F32, flags=flags, eps=cfg.eps,
+              window_reduce=P.CKV_MEAN if window_reduce is None else window_reduce, softmax_scale=softmax_scale)
+    kw.update(over)
+    return P.make_desc(**kw)
+
+
+def to_device(cfg, tensors: Dict[str, np.ndarray], wo_out_in: bool, device="cuda"):
+    import torch
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    out = {}
+    for name, a in tensors.items():
+        if name == "w_o" and wo_out_in:
+            a = np.ascontiguousarray(a.T)
+        out[name] = torch.from_numpy(a).to(device=device, dtype=dt).contiguous()
+    return out
+
+
+@dataclass
+class GpuResult:
+    attn: np.ndarray
+    crit: np.ndarray
+    vnorm: Optional[np.ndarray]
+    idx: np.ndarray
+    count: np.ndarray
+    k_out: np.ndarray
+    v_out: np.ndarray
+
+
+def run_gpu_pass(P, cfg, tensors, budget, alpha, *, flags=0, wo_out_in=False, max_budget=None, want_vnorm=True,
+                 window_reduce=None, softmax_scale=0.0, dev=None) -> GpuResult:
+    """score -> select -> compact through the C ABI on cuda:0; returns host copies."""
+    import torch
+    if wo_out_in:
+        flags |= P.CKV_WO_OUT_IN
+    desc = cfg_desc(P, cfg, flags=flags, window_reduce=window_reduce, softmax_scale=softmax_scale)
+    dev = dev or to_device(cfg, tensors, wo_out_in)
+    b, H, Hkv, n, dh = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_ctx, cfg.head_dim
+    budget = np.broadcast_to(np.asarray(budget, dtype=np.int32), (b, Hkv)).copy()
+    if max_budget is None:
+        max_budget = max(1, int(budget.max()))
+    ws = torch.empty(P.workspace_bytes(desc, max_budget), dtype=torch.uint8, device="cuda")
+    attn = torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda")
+    crit = torch.empty_like(attn)
+    vnorm = torch.empty((b, H, n), dtype=torch.float32, device="cuda") if want_vnorm else None
+    idx = torch.full((b, Hkv, max_budget), -7, dtype=torch.int32, device="cuda")
+    count = torch.full((b, Hkv), -7, dtype=torch.int32, device="cuda")
+    k_out = torch.zeros((b, Hkv, max_budget, dh), dtype=dev["k"].dtype, device="cuda")
+    v_out = torch.zeros_like(k_out)
+    bud = torch.from_numpy(budget).cuda()
+    P.criticalkv_score(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], attn, crit, vnorm, workspace=ws)
+    P.criticalkv_select(desc, attn, crit, bud, alpha, max_budget, idx, count, workspace=ws)
+    P.criticalkv_compact(desc, dev["k"], dev["v"], idx, count, max_budget, k_out, v_out)
+    torch.cuda.synchronize()
+    return GpuResult(attn.cpu().numpy(), crit.cpu().numpy(), None if vnorm is None else vnorm.cpu().numpy(),
+                     idx.cpu().numpy(), count.cpu().numpy(), k_out.float().cpu().numpy(), v_out.float().cpu().numpy())
+
+
+def score_errors(got: np.ndarray, ref: np.ndarray):
+    """max and median relative error with the floor 1e-7 * max|ref| on the denominator."""
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    denom = np.maximum(np.abs(ref), 1e-7 * np.abs(ref).max())
+    rel = np.abs(got - ref) / denom
+    return float(rel.max()), float(np.median(rel))
+
+
+def assert_scores_close(got, ref, what, tol=REL_TOL):
+    mx, med = score_errors(got, ref)
+    assert mx <= tol, f"{what}: max relative error {mx:.3e} > {tol} (median {med:.3e})"
+    return mx, med
+
+
+def compare_selection(idx_gpu, count_gpu, oracle, budget, alpha, tol=REL_TOL):
+    """Set comparison per (batch, kv head) under the tie rule.  Returns the total number of swapped
+    indices (entries in exactly one of the two sets); raises on any difference outside the tolerance band."""
+    b, Hkv, _ = idx_gpu.shape
+    budget = np.broadcast_to(np.asarray(budget, dtype=np.int64), (b, Hkv))
+    swaps = 0
+    for bi in range(b):
+        for g in range(Hkv):
+            B = int(budget[bi, g])
+            assert int(count_gpu[bi, g]) == B, f"count[{bi},{g}] = {count_gpu[bi, g]} != budget {B}"
+            got = idx_gpu[bi, g, :B]
+            assert np.all(idx_gpu[bi, g, B:] == -1), "tail must be -1"
+            assert np.all(np.diff(got) > 0), "indices must be strictly ascending"
+            ref = oracle.idx[bi, g, :B]
+            if np.array_equal(got, ref):
+                continue
+            diff = np.setxor1d(got, ref)
+            tau1, tau2 = oracle.tau[bi, g]
+            a = oracle.attn[bi, g, diff]
+            c = oracle.crit[bi, g, diff]
+            near1 = np.abs(a - tau1) <= tol * abs(tau1) if np.isfinite(tau1) else np.zeros(len(diff), bool)
+            near2 = np.abs(c - tau2) <= tol * abs(tau2) if np.isfinite(tau2) else np.zeros(len(diff), bool)
+            bad = diff[~(near1 | near2)]
+            assert bad.size == 0, (f"head ({bi},{g}): {bad.size} differing indices outside the tolerance band, "
+                                   f"e.g. {bad[:5].tolist()}")
+            swaps += int(diff.size)
+    return swaps
+
+
+def assert_compaction_exact(res: GpuResult, tensors, budget):
+    """k_out / v_out rows are bit-exact copies of the rows idx names (checked against the GPU's own idx)."""
+    b, Hkv, mb = res.idx.shape
+    budget = np.broadcast_to(np.asarray(budget, dtype=np.int64), (b, Hkv))
+    for bi in range(b):
+        for g in range(Hkv):
+            B = int(budget[bi, g])
+            sel = res.idx[bi, g, :B]
+            assert np.array_equal(res.k_out[bi, g, :B], tensors["k"][bi, g, sel])
+            assert np.array_equal(res.v_out[bi, g, :B], tensors["v"][bi, g, sel])
+            assert not res.k_out[bi, g, B:].any() and not res.v_out[bi, g, B:].any(), "rows past count must be untouched"

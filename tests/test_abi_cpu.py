@@ -1,0 +1,121 @@
+"""C-ABI checks that need no GPU: the library loads, exports every declared symbol, and rejects bad
+arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2502_03805_amd as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(P.binding.LIB_PATH):
+        from paper_2502_03805_amd.build import build
+        build()
+    return P.load()
+
+
+def good_desc(**over):
+    kw = dict(batch=1, n_q_heads=8, n_kv_heads=2, head_dim=128, d_model=256, n_ctx=1000, window=16, pool_kernel=7,
+              dtype=P.CKV_BF16)
+    kw.update(over)
+    return P.make_desc(**kw)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "criticalkv.h")).read()
+    declared = set(re.findall(r"CKV_API[^;(]*?\b(criticalkv_\w+)\s*\(", header))
+    assert declared == set(P.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_descriptor_struct_matches_header_layout():
+    # 12 x int32 + 2 x float + 6 x int64, no padding surprises
+    assert ctypes.sizeof(P.LayerDesc) == 12 * 4 + 2 * 4 + 6 * 8
+    assert P.LayerDesc.k_stride.offset == 56 and P.LayerDesc.v_stride.offset == 80
+
+
+def test_strerror_is_static_text(lib):
+    for code in (0, -1, -2, -3, -4, -99):
+        s = P.strerror(code)
+        assert isinstance(s, str) and len(s) > 3
+
+
+def test_workspace_bytes_is_positive_and_monotone(lib):
+    a = P.workspace_bytes(good_desc(n_ctx=1000), 100)
+    b = P.workspace_bytes(good_desc(n_ctx=2000), 100)
+    assert 0 < a < b and a % 256 == 0
+    assert P.workspace_bytes(good_desc(n_ctx=0), 1) == 0
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(batch=0), P.CKV_E_INVALID_ARG),
+    (dict(n_q_heads=7), P.CKV_E_INVALID_ARG),          # H % Hkv != 0
+    (dict(window=0), P.CKV_E_INVALID_ARG),
+    (dict(window=2000), P.CKV_E_INVALID_ARG),          # W > n
+    (dict(pool_kernel=4), P.CKV_E_INVALID_ARG),        # even pooling width
+    (dict(dtype=5), P.CKV_E_INVALID_ARG),
+    (dict(window_reduce=3), P.CKV_E_INVALID_ARG),
+    (dict(flags=64), P.CKV_E_INVALID_ARG),
+    (dict(softmax_scale=-1.0), P.CKV_E_INVALID_ARG),
+    (dict(eps=float("nan")), P.CKV_E_INVALID_ARG),
+    (dict(head_dim=96), P.CKV_E_UNSUPPORTED),
+    (dict(d_model=100), P.CKV_E_UNSUPPORTED),
+    (dict(norm=2), P.CKV_E_UNSUPPORTED),
+    (dict(k_stride=(128000, 64000, 100)), P.CKV_E_INVALID_ARG),   # token stride below head_dim
+    (dict(k_stride=(128004, 64004, 132)), P.CKV_E_UNSUPPORTED),   # rows not 16-byte aligned
+])
+def test_bad_descriptors_are_rejected_without_a_device(lib, over, code):
+    d = good_desc(**over)
+    buf = ctypes.create_string_buffer(512)  # never dereferenced: validation fails first
+    p = ctypes.addressof(buf)
+    p = (p + 255) & ~255
+    rc = lib.criticalkv_score(ctypes.byref(d), p, p, p, p, p, p, None, p, 1 << 40, None)
+    assert rc == code
+    rc = lib.criticalkv_compact(ctypes.byref(d), p, p, p, p, 10, p, p, None)
+    assert rc == code
+
+
+def test_null_pointers_workspace_and_ranges(lib):
+    d = good_desc()
+    need = P.workspace_bytes(d, 100)
+    buf = ctypes.create_string_buffer(1024)
+    p = (ctypes.addressof(buf) + 255) & ~255
+    # null tensor
+    assert lib.criticalkv_score(ctypes.byref(d), None, p, p, p, p, p, None, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_score(None, p, p, p, p, p, p, None, p, need, None) == P.CKV_E_INVALID_ARG
+    # workspace missing / misaligned / too small
+    assert lib.criticalkv_score(ctypes.byref(d), p, p, p, p, p, p, None, None, need, None) == P.CKV_E_WORKSPACE
+    assert lib.criticalkv_score(ctypes.byref(d), p, p, p, p, p, p, None, p + 8, need, None) == P.CKV_E_WORKSPACE
+    assert lib.criticalkv_score(ctypes.byref(d), p, p, p, p, p, p, None, p, need - 1, None) == P.CKV_E_WORKSPACE
+    # select: alpha and max_budget ranges
+    assert lib.criticalkv_select(ctypes.byref(d), p, p, p, 1.5, 100, p, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_select(ctypes.byref(d), p, p, p, float("nan"), 100, p, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_select(ctypes.byref(d), p, p, p, 0.5, 0, p, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_select(ctypes.byref(d), p, p, p, 0.5, 1001, p, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_select(ctypes.byref(d), p, p, None, 0.5, 100, p, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_select(ctypes.byref(d), p, p, p, 0.5, 100, p, p, p, 16, None) == P.CKV_E_WORKSPACE
+    assert lib.criticalkv_compact(ctypes.byref(d), p, p, p, p, 0, p, p, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_compact(ctypes.byref(d), p, p, p, None, 10, p, p, None) == P.CKV_E_INVALID_ARG
+
+
+def test_binding_raises_with_code():
+    d = good_desc(head_dim=96)
+
+    class Fake:
+        def data_ptr(self): return 256
+        def numel(self): return 1 << 30
+        def element_size(self): return 1
+
+    class FakeStream:
+        cuda_stream = 0
+
+    f = Fake()
+    with pytest.raises(P.CriticalKVError) as e:
+        P.criticalkv_score(d, f, f, f, f, f, f, None, workspace=f, stream=FakeStream())
+    assert e.value.code == P.CKV_E_UNSUPPORTED
