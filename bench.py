@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-layer KV-cache selection pass on one MI355X.
+
+A step is one whole pass (criticalkv_score -> criticalkv_select -> criticalkv_compact) over one
+synthetic layer whose inputs are already resident in HBM.  Prints ONE JSON line:
+metric = M KV entries scored+selected per second (one entry = one (batch item, kv head, token)),
+with the roofline of the dominant kernel (the bf16 MFMA projection ||V W^O||_1) and the float64 CPU
+oracle timed on a bounded sample of the same workload as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+class HipEvents:
+    """hipEvent_t handles from the process's HIP runtime (recorded by the library on the launch stream)."""
+
+    def __init__(self, hip):
+        self.hip = hip
+        hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.made = []
+
+    def new(self):
+        e = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(e))
+        assert rc == 0 and e.value, f"hipEventCreate failed ({rc})"
+        self.made.append(e)
+        return e
+
+    def record(self, e, stream):
+        rc = self.hip.hipEventRecord(e, stream)
+        assert rc == 0, f"hipEventRecord failed ({rc})"
+
+    def ms(self, a, b):
+        out = ctypes.c_float()
+        rc = self.hip.hipEventSynchronize(b)
+        assert rc == 0
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(out), a, b)
+        assert rc == 0, f"hipEventElapsedTime failed ({rc})"
+        return float(out.value)
+
+    def close(self):
+        for e in self.made:
+            self.hip.hipEventDestroy(e)
+        self.made = []
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama32k", help="llama32k (default) | llama128k | qwen128k | mistral_prefill | tiny")
+    ap.add_argument("--sets", type=int, default=0, help="independent input sets rotated over the steps (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=12288)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build targets ONE MI355X; the pass shards by kv head / batch item with no "
+              "exchange, and no multi-GPU path is built. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    import paper_2502_03805_amd as P
+    from helpers import cfg_desc, to_device
+    from workload import CONFIGS, make_layer
+
+    P.load()
+    cfg = CONFIGS[args.workload]
+    b, H, Hkv, n, dh, dm = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_ctx, cfg.head_dim, cfg.d_model
+    esize = 2 if cfg.dtype == "bf16" else 4
+    kv_bytes = 2 * b * Hkv * n * dh * esize
+    # rotate enough input sets that K and V of consecutive steps cannot sit in the 256 MB Infinity Cache
+    nsets = args.sets or max(2, min(4, int(np.ceil(512e6 / kv_bytes))))
+    desc = cfg_desc(P, cfg, flags=P.CKV_WO_OUT_IN)
+    B = cfg.budget
+    ws = torch.empty(P.workspace_bytes(desc, B), dtype=torch.uint8, device="cuda")
+    sets = []
+    host0 = None
+    for s in range(nsets):
+        t = make_layer(cfg, layer=0, seed_offset=s)
+        if s == 0:
+            host0 = t
+        dev = to_device(cfg, t, True)
+        if s > 0:
+            dev["w_o"] = sets[0]["w_o"]  # the projection is a weight: one copy
+        sets.append(dev)
+    attn = torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda")
+    crit = torch.empty_like(attn)
+    idx = torch.empty((b, Hkv, B), dtype=torch.int32, device="cuda")
+    count = torch.empty((b, Hkv), dtype=torch.int32, device="cuda")
+    k_out = torch.empty((b, Hkv, B, dh), dtype=sets[0]["k"].dtype, device="cuda")
+    v_out = torch.empty_like(k_out)
+    budget = torch.full((b, Hkv), B, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream or None
+    ev = HipEvents(P.hip_runtime())
+    n_slots = 2 * len(P.STAGES)
+
+    def one_pass(dev, stage_events):
+        P.criticalkv_score_profiled(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], attn, crit, None,
+                                    workspace=ws, stage_events=stage_events, stream=stream)
+        P.criticalkv_select(desc, attn, crit, budget, cfg.alpha, B, idx, count, workspace=ws, stream=stream)
+        P.criticalkv_compact(desc, dev["k"], dev["v"], idx, count, B, k_out, v_out, stream=stream)
+
+    none_events = (ctypes.c_void_p * n_slots)()
+    for w in range(args.warmup):
+        one_pass(sets[w % nsets], none_events)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps; only the dominant kernel carries event marks --------------------
+    vslot = 2 * P.STAGES.index("vproj")
+    step_events = []
+    for _ in range(args.steps):
+        arr = (ctypes.c_void_p * n_slots)()
+        arr[vslot], arr[vslot + 1] = ev.new(), ev.new()
+        step_events.append(arr)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        one_pass(sets[s % nsets], step_events[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    vproj_ms = [ev.ms(ctypes.c_void_p(a[vslot]), ctypes.c_void_p(a[vslot + 1])) for a in step_events]
+    vproj_avg = float(np.mean(vproj_ms))
+    assert int(count.min()) == B and int(count.max()) == B
+
+    # ---- untimed extra passes: per-stage breakdown -------------------------------------------------------
+    stage_ms = {name: [] for name in P.STAGES}
+    stage_ms["select"], stage_ms["compact"] = [], []
+    for s in range(min(5, max(2, args.steps))):
+        dev = sets[s % nsets]
+        arr = (ctypes.c_void_p * n_slots)()
+        for j in range(n_slots):
+            arr[j] = ev.new()
+        e_sel0, e_sel1, e_cp1 = ev.new(), ev.new(), ev.new()
+        P.criticalkv_score_profiled(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], attn, crit, None,
+                                    workspace=ws, stage_events=arr, stream=stream)
+        ev.record(e_sel0, sh)
+        P.criticalkv_select(desc, attn, crit, budget, cfg.alpha, B, idx, count, workspace=ws, stream=stream)
+        ev.record(e_sel1, sh)
+        P.criticalkv_compact(desc, dev["k"], dev["v"], idx, count, B, k_out, v_out, stream=stream)
+        ev.record(e_cp1, sh)
+        torch.cuda.synchronize()
+        for i, name in enumerate(P.STAGES):
+            stage_ms[name].append(ev.ms(ctypes.c_void_p(arr[2 * i]), ctypes.c_void_p(arr[2 * i + 1])))
+        stage_ms["select"].append(ev.ms(e_sel0, e_sel1))
+        stage_ms["compact"].append(ev.ms(e_sel1, e_cp1))
+    stage_ms = {k: round(float(np.median(v)), 4) for k, v in stage_ms.items()}
+    ev.close()
+
+    entries = cfg.entries
+    value = entries / (ms_per_step * 1e-3) / 1e6
+    flops = 2.0 * b * H * n * dh * dm
+    achieved = flops / (vproj_avg * 1e-3) / 1e12
+    # lower bound of the whole pass: K and V read once, W_O once, the MFMA contraction, the gather traffic
+    hbm_bytes = (kv_bytes                      # K and V read once
+                 + H * dh * dm * esize           # W_O read once
+                 + 2 * 4.0 * b * Hkv * n         # attn, crit written
+                 + 2 * 4.0 * b * Hkv * n         # and read by the selection
+                 + 2.0 * kv_bytes * B / n)       # kept rows read and written
+    t_bound_ms = (flops / (PEAK_BF16_TFLOPS * 1e12) + hbm_bytes / (PEAK_HBM_GBS * 1e9)) * 1e3
+    out = {
+        "metric": "M KV entries scored+selected per second (whole score->select->compact pass, one layer)",
+        "value": round(value, 2), "unit": "M KV entries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: batch {b}, {H} q / {Hkv} kv heads, d_h {dh}, d_model {dm}, n {n}, "
+                               f"W {cfg.window}, pool {cfg.pool_kernel}, budget {B}/head, alpha {cfg.alpha}",
+                   "w_o_layout": "[d_model, H*d_h] (CKV_WO_OUT_IN)", "input_sets_rotated": nsets,
+                   "tokens_per_s": round(b * n / (ms_per_step * 1e-3), 1)},
+        "roofline": {"kernel": "vproj_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None, "avg_launch_ms": round(vproj_avg, 4),
+                     "algorithmic_flop_per_launch": flops},
+        "stages_ms": stage_ms,
+        "pass_lower_bound_ms": round(t_bound_ms, 4), "pass_frac_of_bound": round(t_bound_ms / ms_per_step, 4),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import cpu_oracle as O
+        ns = min(n, args.cpu_sample_tokens)
+        Bs = max(1, int(round(B * ns / n)))
+        sample = {k: (v[:, :, :ns] if k in ("k", "v") else v) for k, v in host0.items()}
+        O.lib()
+        c0 = time.perf_counter()
+        O.full_pass(sample["q_win"], sample["k"], sample["v"], sample["w_o"], Bs, cfg.alpha,
+                    pool_kernel=cfg.pool_kernel, eps=cfg.eps)
+        c1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": round(b * Hkv * ns / (c1 - c0) / 1e6, 4), "unit": "M KV entries/s",
+                               "cores": O.num_threads(), "kind": "oracle",
+                               "sample": f"first {ns} tokens of every kv head of input set 0, whole pass "
+                                         f"(budget {Bs}/head), {c1 - c0:.1f} s wall"}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

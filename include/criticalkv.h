@@ -121,6 +121,22 @@ CKV_API int criticalkv_score(const ckv_layer_desc *desc, const void *q_win, cons
                              size_t workspace_bytes, void *hip_stream);
 
 /*
+ * criticalkv_score with per-stage timing marks, for benchmarks and profiles (the scores are the same).
+ * stage_events is a HOST array of 2 * CKV_N_SCORE_STAGES hipEvent_t (as void*) created by the caller with
+ * timing enabled; entry 2*s is recorded on the stream before stage s, entry 2*s+1 after it.  NULL entries
+ * (or a NULL array) are skipped.  The caller reads the events after synchronising.
+ */
+#define CKV_STAGE_WO_LAYOUT 0   /* layout change of a canonical w_o (empty with CKV_WO_OUT_IN) */
+#define CKV_STAGE_ATTN_STATS 1  /* first key sweep: row max and sum of exp                      */
+#define CKV_STAGE_ATTN_COLSUM 2 /* second key sweep: window-reduced softmax weights             */
+#define CKV_STAGE_VPROJ 3       /* ||V W^O||_1 per entry                                        */
+#define CKV_STAGE_COMBINE 4     /* pooling, eps, product, group mean                            */
+#define CKV_N_SCORE_STAGES 5
+CKV_API int criticalkv_score_profiled(const ckv_layer_desc *desc, const void *q_win, const void *k, const void *v,
+                                      const void *w_o, float *attn, float *crit, float *vnorm_opt, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream, void *const *stage_events);
+
+/*
  * Two-stage selection per (batch item, kv head) (Algorithm 1 lines 4-9).
  *
  *   B   = clamp(budget[bi,g], 0, min(n, max_budget))

@@ -5,5 +5,5 @@ include/criticalkv.h); this package is its ctypes binding.
 """
 from .binding import (CKV_BF16, CKV_F32, CKV_MEAN, CKV_SUM, CKV_NORM_L1, CKV_WO_OUT_IN, CKV_NO_MFMA,  # noqa: F401
                       CKV_OK, CKV_E_INVALID_ARG, CKV_E_UNSUPPORTED, CKV_E_WORKSPACE, CKV_E_HIP, EXPORTS,
-                      CriticalKVError, LayerDesc, criticalkv_compact, criticalkv_score, criticalkv_select, load,
+                      CriticalKVError, LayerDesc, hip_runtime, criticalkv_compact, criticalkv_score, criticalkv_score_profiled, criticalkv_select, load, STAGES,
                       make_desc, strerror, workspace_bytes)

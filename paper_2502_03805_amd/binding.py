@@ -20,8 +20,9 @@ CKV_MEAN, CKV_SUM = 0, 1
 CKV_WO_OUT_IN, CKV_NO_MFMA = 1, 2
 CKV_OK, CKV_E_INVALID_ARG, CKV_E_UNSUPPORTED, CKV_E_WORKSPACE, CKV_E_HIP = 0, -1, -2, -3, -4
 
-EXPORTS = ("criticalkv_workspace_bytes", "criticalkv_score", "criticalkv_select", "criticalkv_compact",
-           "criticalkv_strerror")
+EXPORTS = ("criticalkv_workspace_bytes", "criticalkv_score", "criticalkv_score_profiled", "criticalkv_select",
+           "criticalkv_compact", "criticalkv_strerror")
+STAGES = ("wo_layout", "attn_stats", "attn_colsum", "vproj", "combine")
 
 
 class LayerDesc(ctypes.Structure):
@@ -43,6 +44,24 @@ class CriticalKVError(RuntimeError):
 
 
 _lib = None
+_hip = None
+
+
+def hip_runtime() -> ctypes.CDLL:
+    """The process's single HIP runtime, made visible to libcriticalkv.so.
+
+    libcriticalkv.so is linked without a HIP dependency so that it binds to the runtime PyTorch
+    already uses: device pointers, streams and events then belong to one runtime.  PyTorch ships its
+    own copy (torch/lib/libamdhip64.so); it is opened again here with RTLD_GLOBAL, which returns the
+    loaded instance and exposes its symbols."""
+    global _hip
+    if _hip is None:
+        import torch  # device memory and streams come from PyTorch; importing it first loads its HIP runtime
+        path = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+        if not os.path.exists(path):
+            raise ImportError(f"PyTorch-ROCm's HIP runtime not found at {path}")
+        _hip = ctypes.CDLL(path, mode=ctypes.RTLD_GLOBAL)
+    return _hip
 
 
 def load() -> ctypes.CDLL:
@@ -52,6 +71,7 @@ def load() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2502_03805_amd.build` "
                               "(or __graft_entry__.build()) first")
+        hip_runtime()
         lib = ctypes.CDLL(LIB_PATH)
         vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
         dp = ctypes.POINTER(LayerDesc)
@@ -59,6 +79,9 @@ def load() -> ctypes.CDLL:
         lib.criticalkv_workspace_bytes.argtypes = [dp, i32]
         lib.criticalkv_score.restype = ctypes.c_int
         lib.criticalkv_score.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.criticalkv_score_profiled.restype = ctypes.c_int
+        lib.criticalkv_score_profiled.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp,
+                                                  ctypes.POINTER(ctypes.c_void_p)]
         lib.criticalkv_select.restype = ctypes.c_int
         lib.criticalkv_select.argtypes = [dp, vp, vp, vp, f32, i32, vp, vp, vp, ctypes.c_size_t, vp]
         lib.criticalkv_compact.restype = ctypes.c_int
@@ -106,6 +129,16 @@ def criticalkv_score(desc: LayerDesc, q_win, k, v, w_o, attn, crit, vnorm=None, 
                                  _stream(stream))
     if rc != CKV_OK:
         raise CriticalKVError(rc, "criticalkv_score")
+
+
+def criticalkv_score_profiled(desc: LayerDesc, q_win, k, v, w_o, attn, crit, vnorm=None, *, workspace, stage_events,
+                              stream=None) -> None:
+    """stage_events: ctypes array (c_void_p * (2 * len(STAGES))) of hipEvent_t handles, NULL = skip."""
+    rc = load().criticalkv_score_profiled(ctypes.byref(desc), _ptr(q_win), _ptr(k), _ptr(v), _ptr(w_o), _ptr(attn),
+                                          _ptr(crit), _ptr(vnorm), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream), stage_events)
+    if rc != CKV_OK:
+        raise CriticalKVError(rc, "criticalkv_score_profiled")
 
 
 def criticalkv_select(desc: LayerDesc, attn, crit, budget, alpha: float, max_budget: int, idx, count, *, workspace,

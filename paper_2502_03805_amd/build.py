@@ -52,7 +52,9 @@ def build(force: bool = True, verbose: bool = False, extra=()) -> str:
             print(f"--- {src}\n{out}")
     if failed:
         raise RuntimeError("hipcc failed")
-    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    # Linked WITHOUT a dependency on a HIP runtime: the process that loads the library must already hold
+    # one (the binding loads PyTorch's own copy first), so kernels, streams and events live in a single runtime.
+    subprocess.check_call(["g++", "-shared", "-fPIC", "-o", LIB, *objs])
     return LIB
 
 

@@ -89,9 +89,14 @@ size_t criticalkv_workspace_bytes(const ckv_layer_desc *desc, int32_t max_budget
     return carve_workspace(d, desc->dtype, true).total;
 }
 
-int criticalkv_score(const ckv_layer_desc *desc, const void *q_win, const void *k, const void *v, const void *w_o,
-                     float *attn, float *crit, float *vnorm_opt, void *workspace, size_t workspace_bytes,
-                     void *hip_stream)
+static void mark(void *const *ev, int slot, hipStream_t s)
+{
+    if (ev && ev[slot]) (void)hipEventRecord((hipEvent_t)ev[slot], s);
+}
+
+static int score_impl(const ckv_layer_desc *desc, const void *q_win, const void *k, const void *v, const void *w_o,
+                      float *attn, float *crit, float *vnorm_opt, void *workspace, size_t workspace_bytes,
+                      void *hip_stream, void *const *ev)
 {
     Dims d;
     int rc = resolve(desc, &d);
@@ -109,29 +114,54 @@ int criticalkv_score(const ckv_layer_desc *desc, const void *q_win, const void *
     float *stats = (float *)(base + ws.stats);
     const void *w_t = w_o;
     hipError_t e;
+    mark(ev, 2 * CKV_STAGE_WO_LAYOUT, s);
     if (need_wt) {
         e = launch_transpose_wo(d, desc->dtype, w_o, base + ws.w_t, s);
         if (e != hipSuccess) return CKV_E_HIP;
         w_t = base + ws.w_t;
     }
+    mark(ev, 2 * CKV_STAGE_WO_LAYOUT + 1, s);
     const bool mfma_a = mfma_allowed(desc) && attn_mfma_supported(d);
     const bool mfma_v = mfma_allowed(desc) && vproj_mfma_supported(d);
     const int chunks = mfma_a ? mfma_attn_chunks(d) : generic_attn_chunks(d);
     if (chunks > ws.max_chunks) return CKV_E_WORKSPACE;
 
+    mark(ev, 2 * CKV_STAGE_ATTN_STATS, s);
     e = mfma_a ? launch_attn_stats_mfma(d, q_win, k, part, chunks, s)
                : launch_attn_stats_generic(d, desc->dtype, q_win, k, part, chunks, s);
     if (e != hipSuccess) return CKV_E_HIP;
     e = launch_attn_stats_reduce(d, part, chunks, stats, s);
     if (e != hipSuccess) return CKV_E_HIP;
+    mark(ev, 2 * CKV_STAGE_ATTN_STATS + 1, s);
+    mark(ev, 2 * CKV_STAGE_ATTN_COLSUM, s);
     e = mfma_a ? launch_attn_colsum_mfma(d, q_win, k, stats, a_raw, s)
                : launch_attn_colsum_generic(d, desc->dtype, q_win, k, stats, a_raw, s);
     if (e != hipSuccess) return CKV_E_HIP;
+    mark(ev, 2 * CKV_STAGE_ATTN_COLSUM + 1, s);
+    mark(ev, 2 * CKV_STAGE_VPROJ, s);
     e = mfma_v ? launch_vproj_mfma(d, v, w_t, vnorm, s) : launch_vproj_generic(d, desc->dtype, v, w_t, vnorm, s);
     if (e != hipSuccess) return CKV_E_HIP;
+    mark(ev, 2 * CKV_STAGE_VPROJ + 1, s);
+    mark(ev, 2 * CKV_STAGE_COMBINE, s);
     e = launch_combine(d, a_raw, vnorm, attn, crit, s);
     if (e != hipSuccess) return CKV_E_HIP;
+    mark(ev, 2 * CKV_STAGE_COMBINE + 1, s);
     return CKV_OK;
+}
+
+int criticalkv_score(const ckv_layer_desc *desc, const void *q_win, const void *k, const void *v, const void *w_o,
+                     float *attn, float *crit, float *vnorm_opt, void *workspace, size_t workspace_bytes,
+                     void *hip_stream)
+{
+    return score_impl(desc, q_win, k, v, w_o, attn, crit, vnorm_opt, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+int criticalkv_score_profiled(const ckv_layer_desc *desc, const void *q_win, const void *k, const void *v,
+                              const void *w_o, float *attn, float *crit, float *vnorm_opt, void *workspace,
+                              size_t workspace_bytes, void *hip_stream, void *const *stage_events)
+{
+    return score_impl(desc, q_win, k, v, w_o, attn, crit, vnorm_opt, workspace, workspace_bytes, hip_stream,
+                      stage_events);
 }
 
 int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float *crit, const int32_t *budget,

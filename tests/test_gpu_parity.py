@@ -250,3 +250,22 @@ def test_full_size_sampled(P, name):
     assert np.array_equal(res.count, ref_count) and np.array_equal(res.idx, ref_idx)
     assert_compaction_exact(res, t, cfg.budget)
     print(f"[{name} full] max rel err attn {e_a[0]:.2e} vnorm {e_v[0]:.2e} crit {e_c[0]:.2e} on {rows.size} sampled tokens")
+
+
+# ------------------------------------------------------------------------------------------------ runtime plumbing
+def test_single_hip_runtime_and_side_stream(P):
+    """The library must run in PyTorch's HIP runtime (one libamdhip64 mapped) and honour a non-default stream."""
+    import torch
+    mapped = {line.split()[-1] for line in open("/proc/self/maps") if "libamdhip64" in line}
+    assert len(mapped) == 1, mapped
+    loaded = [line.split()[-1] for line in open("/proc/self/maps") if "libcriticalkv.so" in line]
+    assert loaded, "the HIP extension is not loaded"
+    cfg = reduced(CONFIGS["llama32k"], 2048, d_model=512)
+    t = make_layer(cfg)
+    ref = oracle_pass(cfg, t)
+    side = torch.cuda.Stream()
+    assert side.cuda_stream != 0
+    with torch.cuda.stream(side):
+        res = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, wo_out_in=True)
+    assert_scores_close(res.crit, ref.crit, "crit(side stream)")
+    compare_selection(res.idx, res.count, ref, cfg.budget, cfg.alpha)
