@@ -6,16 +6,20 @@
 // folded into per-row partial sums by the epilogue and never reach memory.
 //
 // Tiling (d_h = 128):
-//   workgroup = 4 waves; wave w owns R blocks of 32 token rows; their V fragments (the MFMA A
-//   operand, 8 k-steps of 16) stay in registers for the whole kernel: V is read once.
-//   The head's W_O slice, stored output-major ([d_model][H*d_h], so the 128 inner-dimension
-//   values of one output column are contiguous), streams through LDS in tiles of TN columns,
-//   double buffered; each wave reads the B fragments of a 32-column block once and reuses them
-//   for its R row blocks.
-//   v_mfma_f32_32x32x16_bf16: a lane holds 8 consecutive k of row/column (lane % 32), k offset
-//   8 * (lane / 32); accumulator register j of a lane is row 8*(j/4) + 4*(lane/32) + j%4,
-//   column lane % 32.  The epilogue adds |acc[j]| into 16 per-lane row sums per block; lanes
-//   are merged once at the end.
+//   * workgroup = 4 waves, two workgroups per CU; wave w owns R blocks of 32 token rows whose V
+//     fragments (MFMA A operand, 8 k-steps of 16) stay in registers for the whole kernel: V is
+//     read once.
+//   * the head's W_O slice, stored output-major ([d_model][H*d_h]: the 128 inner-dimension values
+//     of an output column are contiguous), streams through LDS in tiles of TN columns, double
+//     buffered, with direct global->LDS loads (no staging registers).  A wave-level direct load
+//     fills 1 KiB of consecutive LDS, so the tile is unpadded [TN][256 B]; bank conflicts of the
+//     fragment reads are avoided by storing 16-byte chunk q of column c at slot q ^ (c & 15).
+//   * v_mfma_f32_32x32x16_bf16: a lane holds 8 consecutive k of row/column (lane % 32) at k offset
+//     8 * (lane / 32); accumulator register j of a lane is row 8*(j/4) + 4*(lane/32) + j%4,
+//     column lane % 32.
+//   * software pipeline per 32-column block: 16 MFMAs into one accumulator set while the previous
+//     set is drained with sum += |acc| (one VALU op per product) and the next block's B fragments
+//     are fetched from LDS.  sched_barrier fences keep this order through the compiler's scheduler.
 #include "common.hpp"
 
 namespace ckv {
@@ -26,17 +30,22 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int VM_THREADS = 256;
 constexpr int VM_WAVES = 4;
 constexpr int VM_DH = 128;
-constexpr int VM_TN = 128;                  // W_O columns per LDS tile
-constexpr int VM_ROW_BYTES = VM_DH * 2 + 16; // padded LDS pitch of one column's 128 bf16
-constexpr int VM_TILE_BYTES = VM_TN * VM_ROW_BYTES;
+constexpr int VM_TN = 128;                 // W_O columns per LDS tile
+constexpr int VM_COL_BYTES = VM_DH * 2;    // 256 B per column, 16 chunks of 16 B
+constexpr int VM_TILE_BYTES = VM_TN * VM_COL_BYTES;
+constexpr int VM_CB = VM_TN / 32;          // 32-column blocks per tile
+constexpr int VM_LOADS = VM_TILE_BYTES / 1024 / VM_WAVES; // direct loads per wave per tile
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
 template <int R>
-__global__ __launch_bounds__(VM_THREADS) void vproj_mfma_kernel(const bf16_t *__restrict__ v,
-                                                                const bf16_t *__restrict__ w_t,
-                                                                float *__restrict__ vnorm, int H, int G, int n, int dm,
-                                                                int64_t vs0, int64_t vs1, int64_t vs2)
+__global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t *__restrict__ v,
+                                                                   const bf16_t *__restrict__ w_t,
+                                                                   float *__restrict__ vnorm, int H, int G, int n,
+                                                                   int dm, int64_t vs0, int64_t vs1, int64_t vs2)
 {
-    __shared__ __attribute__((aligned(16))) char lds[2 * VM_TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds[2 * VM_TILE_BYTES];
     const int h = blockIdx.y, bi = blockIdx.z, g = h / G;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -59,50 +68,86 @@ __global__ __launch_bounds__(VM_THREADS) void vproj_mfma_kernel(const bf16_t *__
 #pragma unroll
         for (int j = 0; j < 16; ++j) sum[r][j] = 0.f;
 
-    // global -> LDS staging: thread t moves 16 bytes of column (t / 16 + 16 * j), j = 0..7
-    const size_t ldw = (size_t)H * VM_DH;
-    const bf16_t *wsrc = w_t + (size_t)h * VM_DH + (size_t)(threadIdx.x >> 4) * ldw + (threadIdx.x & 15) * 8;
-    const int lds_dst = (threadIdx.x >> 4) * VM_ROW_BYTES + (threadIdx.x & 15) * 16;
-    uint4 stage[VM_TN / 16];
+    // Direct loads: instruction j of wave w fills LDS KiB m = j * 4 + w of the tile = columns 4m .. 4m+3;
+    // lane i writes slot i % 16 of column 4m + i / 16 and therefore fetches chunk (i % 16) ^ (column & 15).
+    const size_t ldw = (size_t)H * VM_DH; // elements between consecutive output columns
+    const int ld_col = wave * 4 + (lane >> 4);                       // column of this lane for j = 0
+    const bf16_t *ld_src = w_t + (size_t)h * VM_DH + (size_t)ld_col * ldw + (size_t)(((lane & 15) ^ (ld_col & 15)) * 8);
+    // (columns advance by 16 per instruction, which leaves column & 15 and thus the chunk unchanged)
     const int tiles = dm / VM_TN; // host guarantees dm % VM_TN == 0
 
+    auto issue_load = [&](int tile, int j, char *buf) {
+        const bf16_t *src = ld_src + ((size_t)tile * VM_TN + (size_t)j * 16) * ldw;
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(buf + (j * 4 + wave) * 1024), 16, 0, 0);
+    };
+
 #pragma unroll
-    for (int j = 0; j < VM_TN / 16; ++j) stage[j] = *reinterpret_cast<const uint4 *>(wsrc + (size_t)(16 * j) * ldw);
+    for (int j = 0; j < VM_LOADS; ++j) issue_load(0, j, lds);
+
+    // per-lane byte offsets of the 8 B fragments inside a 32-column block
+    int boff[8];
 #pragma unroll
-    for (int j = 0; j < VM_TN / 16; ++j) *reinterpret_cast<uint4 *>(lds + lds_dst + 16 * j * VM_ROW_BYTES) = stage[j];
+    for (int s = 0; s < 8; ++s) boff[s] = l32 * VM_COL_BYTES + (((2 * s + half) ^ (l32 & 15)) * 16);
+
+    f32x16 acc[2][R];
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[p][r][j] = 0.f;
+
     __syncthreads();
+    bf16x8 b[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) b[s] = *reinterpret_cast<const bf16x8 *>(lds + boff[s]);
 
     for (int t = 0; t < tiles; ++t) {
         const char *cur = lds + (t & 1) * VM_TILE_BYTES;
         char *nxt = lds + ((t + 1) & 1) * VM_TILE_BYTES;
-        const bool more = t + 1 < tiles;
-        if (more) {
-            const bf16_t *src = wsrc + (size_t)(t + 1) * VM_TN * ldw;
+        const int tn = min(t + 1, tiles - 1); // the last iteration re-fetches its own tile into the idle buffer
 #pragma unroll
-            for (int j = 0; j < VM_TN / 16; ++j) stage[j] = *reinterpret_cast<const uint4 *>(src + (size_t)(16 * j) * ldw);
-        }
+        for (int cb = 0; cb < VM_CB; ++cb) {
+            const int pp = cb & 1;
 #pragma unroll
-        for (int cb = 0; cb < VM_TN / 32; ++cb) {
-            bf16x8 b[8];
-            const char *bp = cur + (cb * 32 + l32) * VM_ROW_BYTES + half * 16;
+            for (int s = 0; s < 8; ++s) {
+                if ((s & 3) == 0) issue_load(tn, cb * 2 + (s >> 2), nxt);
 #pragma unroll
-            for (int s = 0; s < 8; ++s) b[s] = *reinterpret_cast<const bf16x8 *>(bp + s * 32);
+                for (int r = 0; r < R; ++r) {
+                    if (s == 0) {
+                        const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                        acc[pp][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[r][s], b[s], z, 0, 0, 0);
+                    } else {
+                        acc[pp][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[r][s], b[s], acc[pp][r], 0, 0, 0);
+                    }
+                }
+                if (cb + 1 < VM_CB)
+                    b[s] = *reinterpret_cast<const bf16x8 *>(cur + (cb + 1) * 32 * VM_COL_BYTES + boff[s]);
+                // drain the previous block's accumulators: nothing at s = 0 (their last MFMA has just been
+                // issued), two values per row block at s = 1..6, four at s = 7
+                if (s >= 1) {
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[r][s], b[s], acc, 0, 0, 0);
-#pragma unroll
-                for (int j = 0; j < 16; ++j) sum[r][j] += fabsf(acc[j]);
+                    for (int r = 0; r < R; ++r) {
+                        sum[r][2 * s - 2] += fabsf(acc[pp ^ 1][r][2 * s - 2]);
+                        sum[r][2 * s - 1] += fabsf(acc[pp ^ 1][r][2 * s - 1]);
+                        if (s == 7) {
+                            sum[r][14] += fabsf(acc[pp ^ 1][r][14]);
+                            sum[r][15] += fabsf(acc[pp ^ 1][r][15]);
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        if (more) {
-#pragma unroll
-            for (int j = 0; j < VM_TN / 16; ++j)
-                *reinterpret_cast<uint4 *>(nxt + lds_dst + 16 * j * VM_ROW_BYTES) = stage[j];
-        }
         __syncthreads();
+#pragma unroll
+        for (int s = 0; s < 8; ++s) b[s] = *reinterpret_cast<const bf16x8 *>(nxt + boff[s]);
     }
+    // the last column block is still in acc[(VM_CB - 1) & 1]
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) sum[r][j] += fabsf(acc[(VM_CB - 1) & 1][r][j]);
 
     // merge the 32 column classes (lanes with equal lane / 32) of every row sum
     float *out = vnorm + ((size_t)bi * H + h) * (size_t)n;
