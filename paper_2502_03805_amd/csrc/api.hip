@@ -130,7 +130,8 @@ static int score_impl(const ckv_layer_desc *desc, const void *q_win, const void 
     e = mfma_a ? launch_attn_stats_mfma(d, q_win, k, part, chunks, s)
                : launch_attn_stats_generic(d, desc->dtype, q_win, k, part, chunks, s);
     if (e != hipSuccess) return CKV_E_HIP;
-    e = launch_attn_stats_reduce(d, part, chunks, stats, s);
+    e = mfma_a ? launch_attn_stats_reduce_log2(d, part, chunks, stats, s)
+               : launch_attn_stats_reduce(d, part, chunks, stats, s);
     if (e != hipSuccess) return CKV_E_HIP;
     mark(ev, 2 * CKV_STAGE_ATTN_STATS + 1, s);
     mark(ev, 2 * CKV_STAGE_ATTN_COLSUM, s);

@@ -55,6 +55,8 @@ hipError_t launch_attn_colsum_generic(const Dims &d, int dtype, const void *q, c
                                       float *a_raw, hipStream_t s);
 hipError_t launch_attn_stats_mfma(const Dims &d, const void *q, const void *k, float *part, int chunks,
                                   hipStream_t s);
+// matrix-core path: partials are in the log2 domain; per row E = log2(sum 2^t) (+ log2 W for the mean)
+hipError_t launch_attn_stats_reduce_log2(const Dims &d, const float *part, int chunks, float *stats, hipStream_t s);
 hipError_t launch_attn_colsum_mfma(const Dims &d, const void *q, const void *k, const float *stats, float *a_raw,
                                    hipStream_t s);
 // projected-value L1 norm; w_t is [d_model, H*dh]
