@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--sets", type=int, default=0, help="independent input sets rotated over the steps (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=12288)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known traffic, to scale profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets ONE MI355X; the pass shards by kv head / batch item with no "
@@ -120,6 +122,13 @@ def main():
                                     workspace=ws, stage_events=stage_events, stream=stream)
         P.criticalkv_select(desc, attn, crit, budget, cfg.alpha, B, idx, count, workspace=ws, stream=stream)
         P.criticalkv_compact(desc, dev["k"], dev["v"], idx, count, B, k_out, v_out, stream=stream)
+
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     none_events = (ctypes.c_void_p * n_slots)()
     for w in range(args.warmup):
