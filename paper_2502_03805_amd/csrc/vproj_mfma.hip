@@ -17,8 +17,9 @@
 //   * v_mfma_f32_32x32x16_bf16: a lane holds 8 consecutive k of row/column (lane % 32) at k offset
 //     8 * (lane / 32); accumulator register j of a lane is row 8*(j/4) + 4*(lane/32) + j%4,
 //     column lane % 32.
-//   * software pipeline per 32-column block: 16 MFMAs into one accumulator set while the previous
-//     set is drained with sum += |acc| (one VALU op per product) and the next block's B fragments
+//   * software pipeline per 32-column block: for each row block a chain of 8 dependent MFMAs into
+//     one accumulator set, while the previous column block's set is drained with sum += |acc| (abs
+//     is a source modifier: one VALU op per product, two per MFMA) and the next block's B fragments
 //     are fetched from LDS.  sched_barrier fences keep this order through the compiler's scheduler.
 #include "common.hpp"
 
@@ -70,15 +71,18 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
 
     // Direct loads: instruction j of wave w fills LDS KiB m = j * 4 + w of the tile = columns 4m .. 4m+3;
     // lane i writes slot i % 16 of column 4m + i / 16 and therefore fetches chunk (i % 16) ^ (column & 15).
+    // The loads are buffer loads (not flat/global ones): the compiler then keeps exact LDS wait counts.
     const size_t ldw = (size_t)H * VM_DH; // elements between consecutive output columns
     const int ld_col = wave * 4 + (lane >> 4);                       // column of this lane for j = 0
-    const bf16_t *ld_src = w_t + (size_t)h * VM_DH + (size_t)ld_col * ldw + (size_t)(((lane & 15) ^ (ld_col & 15)) * 8);
+    const uint32_t ld_voff = (uint32_t)(((size_t)h * VM_DH + (size_t)ld_col * ldw + (size_t)(((lane & 15) ^ (ld_col & 15)) * 8)) * 2);
     // (columns advance by 16 per instruction, which leaves column & 15 and thus the chunk unchanged)
-    const int tiles = dm / VM_TN; // host guarantees dm % VM_TN == 0
+    const int tiles = dm / VM_TN; // host guarantees dm % VM_TN == 0 and the whole matrix < 4 GiB
+    const __amdgpu_buffer_rsrc_t w_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)w_t, 0, (int)((size_t)dm * ldw * 2), 0x00020000);
 
     auto issue_load = [&](int tile, int j, char *buf) {
-        const bf16_t *src = ld_src + ((size_t)tile * VM_TN + (size_t)j * 16) * ldw;
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(buf + (j * 4 + wave) * 1024), 16, 0, 0);
+        const uint32_t soff = (uint32_t)(((size_t)tile * VM_TN + (size_t)j * 16) * ldw * 2);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, LDS_PTR(buf + (j * 4 + wave) * 1024), 16, ld_voff, soff, 0, 0);
     };
 
 #pragma unroll
@@ -110,33 +114,27 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
         for (int cb = 0; cb < VM_CB; ++cb) {
             const int pp = cb & 1;
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                if ((s & 3) == 0) issue_load(tn, cb * 2 + (s >> 2), nxt);
+            for (int r = 0; r < R; ++r) {
+                // one accumulator chain at a time: 8 dependent MFMAs issue back to back at full rate,
+                // whereas two chains taken in turns stall on each other
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
+                for (int s = 0; s < 8; ++s) {
+                    if (r == 0 && (s & 3) == 2) issue_load(tn, cb * 2 + (s >> 2), nxt);
                     if (s == 0) {
                         const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                         acc[pp][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[r][s], b[s], z, 0, 0, 0);
                     } else {
                         acc[pp][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[r][s], b[s], acc[pp][r], 0, 0, 0);
                     }
+                    // after its last use in this block, refill the fragment slot for the next block
+                    if (r == R - 1 && cb + 1 < VM_CB)
+                        b[s] = *reinterpret_cast<const bf16x8 *>(cur + (cb + 1) * 32 * VM_COL_BYTES + boff[s]);
+                    // drain the same row block's accumulators of the previous column block (complete
+                    // since R * 8 MFMAs ago): sum += |acc|, two values per MFMA
+                    sum[r][2 * s] += fabsf(acc[pp ^ 1][r][2 * s]);
+                    sum[r][2 * s + 1] += fabsf(acc[pp ^ 1][r][2 * s + 1]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                if (cb + 1 < VM_CB)
-                    b[s] = *reinterpret_cast<const bf16x8 *>(cur + (cb + 1) * 32 * VM_COL_BYTES + boff[s]);
-                // drain the previous block's accumulators: nothing at s = 0 (their last MFMA has just been
-                // issued), two values per row block at s = 1..6, four at s = 7
-                if (s >= 1) {
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        sum[r][2 * s - 2] += fabsf(acc[pp ^ 1][r][2 * s - 2]);
-                        sum[r][2 * s - 1] += fabsf(acc[pp ^ 1][r][2 * s - 1]);
-                        if (s == 7) {
-                            sum[r][14] += fabsf(acc[pp ^ 1][r][14]);
-                            sum[r][15] += fabsf(acc[pp ^ 1][r][15]);
-                        }
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
             }
         }
         __syncthreads();
@@ -170,7 +168,10 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
     }
 }
 
-bool vproj_mfma_supported(const Dims &d) { return d.dh == VM_DH && d.dm % VM_TN == 0; }
+bool vproj_mfma_supported(const Dims &d)
+{
+    return d.dh == VM_DH && d.dm % VM_TN == 0 && (size_t)d.dm * d.H * d.dh * 2 < ((size_t)1 << 31);
+}
 
 hipError_t launch_vproj_mfma(const Dims &d, const void *v, const void *w_t, float *vnorm, hipStream_t s)
 {
