@@ -66,6 +66,7 @@ Workspace carve_workspace(const Dims &d, int dtype, bool need_wt)
     w.stats = off; off = align256(off + (size_t)d.batch * d.H * d.W * 2 * 4);
     w.w_t = off; if (need_wt) off = align256(off + (size_t)d.H * d.dh * d.dm * elem_size(dtype));
     w.sel_keys = off; off = align256(off + (size_t)d.batch * d.Hkv * d.n * 4);
+    w.sel_scratch = off; off = align256(off + select_workspace_words(d.batch * d.Hkv, d.n) * 4);
     w.total = off;
     return w;
 }
@@ -178,7 +179,9 @@ int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float
     const Workspace ws = carve_workspace(d, desc->dtype, false);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
     uint32_t *keys2 = (uint32_t *)((char *)workspace + ws.sel_keys);
-    hipError_t e = launch_select(d, attn, crit, budget, alpha, max_budget, idx, count, keys2, (hipStream_t)hip_stream);
+    uint32_t *scratch = (uint32_t *)((char *)workspace + ws.sel_scratch);
+    hipError_t e = launch_select(d, attn, crit, budget, alpha, max_budget, idx, count, keys2, scratch,
+                                 (hipStream_t)hip_stream);
     return e == hipSuccess ? CKV_OK : CKV_E_HIP;
 }
 

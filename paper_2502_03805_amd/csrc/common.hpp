@@ -32,6 +32,7 @@ struct Workspace {
     size_t stats;      // [batch, H, W, 2] f32: per-row (max + log sum, unused)
     size_t w_t;        // [d_model, H*dh] copy of W_O in output-major layout (when given canonical)
     size_t sel_keys;   // [batch*Hkv, n] u32: stage-2 keys with stage-1 entries marked
+    size_t sel_scratch; // digit histograms, per-head state, per-slice counts of the selection kernels
     size_t total;
     int max_chunks;    // capacity of stats_part per window row
 };
@@ -68,8 +69,10 @@ hipError_t launch_transpose_wo(const Dims &d, int dtype, const void *w_o, void *
 // pool + eps + product + group mean
 hipError_t launch_combine(const Dims &d, const float *a_raw, const float *vnorm, float *attn, float *crit,
                           hipStream_t s);
+size_t select_workspace_words(int heads, int n); // u32 words of histogram / state / per-slice scratch
 hipError_t launch_select(const Dims &d, const float *attn, const float *crit, const int32_t *budget, float alpha,
-                         int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2, hipStream_t s);
+                         int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2, uint32_t *scratch,
+                         hipStream_t s);
 hipError_t launch_compact(const Dims &d, int dtype, const void *k, const void *v, const int32_t *idx,
                           const int32_t *count, int max_budget, void *k_out, void *v_out, hipStream_t s);
 

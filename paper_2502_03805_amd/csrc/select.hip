@@ -1,24 +1,54 @@
-// Budget split and the two Top-k stages (Algorithm 1, lines 4-9), one workgroup per (batch, kv head).
+// Budget split and the two Top-k stages (Algorithm 1, lines 4-9).
 //
 //   b' = floor(alpha * B), b'' = B - b'
 //   S1 = the b' largest attn;  S2 = the b'' largest crit among entries outside S1
 //   idx = S1 u S2 in ascending token order
-// Top-k is an exact order statistic, found by a most-significant-digit radix select on an
-// order-preserving 32-bit image of the float keys (digits of 11, 11 and 10 bits, histograms
-// in LDS).  Equal keys are taken in ascending token order: the threshold key tau and the
-// number r of entries equal to tau that still fit are known after the last digit, and the
-// r-th tie is located with an ordered prefix count over the tokens.
-// Stage 1 membership is materialised once as the stage-2 key array (taken entries carry a
-// reserved key), which the final ordered write reads back.
+// Top-k is an exact order statistic: a most-significant-digit radix select on an order-preserving
+// 32-bit image of the float keys (digits of 11, 11 and 10 bits).  Equal keys are taken in ascending
+// token order: after the last digit the threshold key tau and the number r of entries equal to tau that
+// still fit are known, and the r-th tie is located with ordered prefix counts.
+//
+// A head's n keys are cut into slices of 2048 tokens, one 256-thread workgroup per (slice, head), so the
+// whole chip works on a layer's few heads.  Workgroups only meet at kernel boundaries:
+//   zero      clear the digit histograms
+//   hist 1.0  digit-0 histogram of attn            (LDS histogram per slice, flushed with integer atomics)
+//   hist 1.1  find digit 0, digit-1 histogram of the entries that match it
+//   hist 1.2  find digit 1, digit-2 histogram
+//   ties 1    find digit 2 -> tau1, r1; ties per slice
+//   mark      stage-1 membership (ties ranked through the per-slice counts), stage-2 keys written
+//             (stage-1 entries carry a reserved key), digit-0 histogram of stage 2
+//   hist 2.1, hist 2.2, then
+//   count     tau2, r2; per slice: selected entries and ties
+//   write     ordered write of S1 u S2 from the per-slice counts; -1 tail; count
+// Every decision is integer arithmetic on exact counts, so the result does not depend on scheduling.
 #include "common.hpp"
 
 namespace ckv {
 
-constexpr int SEL_THREADS = 1024;
-constexpr int SEL_WAVES = SEL_THREADS / 64;
-constexpr int SEL_PER_IT = SEL_THREADS * 4;
+constexpr int SEL_THREADS = 256;
+constexpr int SEL_PER_THREAD = 8;
+constexpr int SEL_SLICE = SEL_THREADS * SEL_PER_THREAD; // tokens per workgroup
 constexpr int SEL_BINS = 2048;
 constexpr uint32_t SEL_TAKEN = 0xFFFFFFFFu; // image of no finite float: marks stage-1 entries
+constexpr int DSHIFT0 = 21, DSHIFT1 = 10;
+constexpr uint32_t DMASK0 = 0x7FFu, DMASK1 = 0x7FFu, DMASK2 = 0x3FFu;
+
+// per-head state words
+enum { ST_D0 = 0, ST_A0, ST_D1, ST_A1, ST_TAU, ST_R, ST_WORDS = 8 };
+
+struct SelArgs {
+    const uint32_t *attn; // float bits
+    const uint32_t *crit;
+    const int32_t *budget;
+    uint32_t *keys2;   // [heads][n]
+    uint32_t *hist;    // [heads][2 stages][3 passes][SEL_BINS]
+    uint32_t *state;   // [heads][2 stages][ST_WORDS]
+    uint32_t *slices;  // [heads][3][n_slices]: ties of stage 1, selected (non-tie) count, ties of stage 2
+    int32_t *idx;
+    int32_t *count;
+    double alpha;
+    int n, max_budget, n_slices;
+};
 
 // Monotone map float -> uint32 (larger float, larger key); -0 and +0 share a key.
 __device__ __forceinline__ uint32_t order_key(uint32_t u)
@@ -27,13 +57,20 @@ __device__ __forceinline__ uint32_t order_key(uint32_t u)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+__device__ __forceinline__ void head_budget(const SelArgs &A, int head, int &B, int &b1, int &b2)
+{
+    B = max(0, min(A.budget[head], min(A.n, A.max_budget)));
+    b1 = (int)floor(A.alpha * (double)B);
+    b2 = B - b1;
+}
+
 struct SelShared {
     uint32_t hist[SEL_BINS];
-    uint32_t wave_tot[SEL_WAVES];
+    uint32_t wave_tot[SEL_THREADS / 64];
     uint32_t digit, above;
 };
 
-// Exclusive prefix sum of x over the workgroup in thread order; total in `total`.
+// Exclusive prefix sum over the workgroup in thread order; total in `total`.
 __device__ __forceinline__ uint32_t block_exclusive_scan(SelShared &sh, uint32_t x, uint32_t &total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -48,7 +85,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(SelShared &sh, uint32_t
     __syncthreads();
     uint32_t base = 0, tot = 0;
 #pragma unroll
-    for (int w = 0; w < SEL_WAVES; ++w) {
+    for (int w = 0; w < SEL_THREADS / 64; ++w) {
         const uint32_t t = sh.wave_tot[w];
         if (w < wave) base += t;
         tot += t;
@@ -57,215 +94,341 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(SelShared &sh, uint32_t
     return base + incl - x;
 }
 
-// 4 consecutive 32-bit words starting at i0 (a multiple of 4); words at or beyond n read as 0.
-__device__ __forceinline__ void load4(const uint32_t *base, int i0, int n, bool vec_ok, uint32_t (&out)[4])
+__device__ __forceinline__ uint32_t block_sum(SelShared &sh, uint32_t x)
 {
-    if (vec_ok && i0 + 3 < n) {
-        const uint4 r = *reinterpret_cast<const uint4 *>(base + i0);
-        out[0] = r.x; out[1] = r.y; out[2] = r.z; out[3] = r.w;
+    uint32_t total;
+    (void)block_exclusive_scan(sh, x, total);
+    return total;
+}
+
+// The thread's 8 consecutive words starting at token i0; words at or beyond n read as 0.
+__device__ __forceinline__ void load8(const uint32_t *base, int i0, int n, bool vec_ok, uint32_t (&out)[8])
+{
+    if (vec_ok && i0 + 7 < n) {
+        const uint4 a = *reinterpret_cast<const uint4 *>(base + i0);
+        const uint4 b = *reinterpret_cast<const uint4 *>(base + i0 + 4);
+        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+        out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
     } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) out[j] = (i0 + j < n) ? base[i0 + j] : 0u;
+        for (int j = 0; j < 8; ++j) out[j] = (i0 + j < n) ? base[i0 + j] : 0u;
     }
 }
 
-// Histogram update; the two most frequent digits of a wave are merged into one atomic each,
-// which keeps narrow key distributions from serialising on a handful of bins.
-__device__ __forceinline__ void hist_add(uint32_t *hist, bool active, uint32_t digit)
+// Largest digit d of a global histogram with  #(digit > d) < remaining <= #(digit >= d); also #(digit > d).
+__device__ void find_digit(SelShared &sh, const uint32_t *ghist, int nbins, uint32_t remaining, uint32_t &digit,
+                           uint32_t &above)
 {
+    constexpr int PER = SEL_BINS / SEL_THREADS; // 8 bins per thread, descending order
+    uint32_t h[PER], local = 0;
 #pragma unroll
-    for (int round = 0; round < 2; ++round) {
-        const unsigned long long act = __ballot(active);
-        if (act == 0ull) return;
-        const int leader = __ffsll((long long)act) - 1;
-        const uint32_t ld = __shfl(digit, leader);
-        const bool same = active && digit == ld;
-        const unsigned long long grp = __ballot(same);
-        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[ld], (uint32_t)__popcll(grp));
-        if (same) active = false;
+    for (int j = 0; j < PER; ++j) {
+        const int bin = nbins - 1 - (threadIdx.x * PER + j);
+        h[j] = bin >= 0 ? ghist[bin] : 0u;
+        local += h[j];
     }
-    if (active) atomicAdd(&hist[digit], 1u);
-}
-
-// One digit of the radix select: histogram of digit (key >> shift) & mask over the entries whose
-// higher digits equal `prefix`.  FROM_FLOAT: src holds floats; otherwise order keys where
-// SEL_TAKEN entries are skipped.
-template <bool FROM_FLOAT>
-__device__ void radix_hist(SelShared &sh, const uint32_t *src, int n, bool vec_ok, int shift, uint32_t mask,
-                           uint32_t prefix_mask, uint32_t prefix)
-{
-    for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS) sh.hist[b] = 0u;
-    __syncthreads();
-    for (int base = 0; base < n; base += SEL_PER_IT) {
-        const int i0 = base + threadIdx.x * 4;
-        uint32_t w[4];
-        load4(src, i0, n, vec_ok, w);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t key = FROM_FLOAT ? order_key(w[j]) : w[j];
-            const bool on = (i0 + j < n) && key != SEL_TAKEN && (key & prefix_mask) == prefix;
-            hist_add(sh.hist, on, (key >> shift) & mask);
-        }
-    }
-    __syncthreads();
-}
-
-// Largest digit d with  #(digit > d) < remaining <= #(digit >= d).  Returns d and #(digit > d).
-__device__ void find_digit(SelShared &sh, int nbins, uint32_t remaining, uint32_t &digit, uint32_t &above)
-{
-    const int rb = 2 * threadIdx.x; // bins in descending order, two per thread
-    const int b0 = nbins - 1 - rb, b1 = b0 - 1;
-    const uint32_t h0 = rb < nbins ? sh.hist[b0] : 0u;
-    const uint32_t h1 = rb + 1 < nbins ? sh.hist[b1] : 0u;
     if (threadIdx.x == 0) { sh.digit = 0u; sh.above = 0u; }
     uint32_t total;
-    const uint32_t excl = block_exclusive_scan(sh, h0 + h1, total);
-    if (excl < remaining && remaining <= excl + h0) { sh.digit = (uint32_t)b0; sh.above = excl; }
-    else if (excl + h0 < remaining && remaining <= excl + h0 + h1) { sh.digit = (uint32_t)b1; sh.above = excl + h0; }
+    uint32_t run = block_exclusive_scan(sh, local, total);
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        if (run < remaining && remaining <= run + h[j]) {
+            sh.digit = (uint32_t)(nbins - 1 - (threadIdx.x * PER + j));
+            sh.above = run;
+        }
+        run += h[j];
+    }
     __syncthreads();
     digit = sh.digit;
     above = sh.above;
     __syncthreads();
 }
 
-constexpr int DSHIFT0 = 21, DSHIFT1 = 10, DSHIFT2 = 0;
-constexpr uint32_t DMASK0 = 0x7FFu, DMASK1 = 0x7FFu, DMASK2 = 0x3FFu;
+__global__ __launch_bounds__(256) void select_zero_kernel(uint32_t *p, size_t words)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < words) p[i] = 0u;
+}
 
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float *__restrict__ attn, const float *__restrict__ crit,
-                                                             const int32_t *__restrict__ budget, double alpha, int n,
-                                                             int max_budget, int32_t *__restrict__ idx,
-                                                             int32_t *__restrict__ count, uint32_t *__restrict__ keys2)
+// Histogram of one digit over a slice.  STAGE 0 reads attn floats, STAGE 1 the stage-2 key array.
+// PASS 0 histograms digit 0 of every entry; PASS 1 / 2 first decode the previous digit(s) of the threshold.
+template <int STAGE, int PASS>
+__global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelArgs A)
 {
     __shared__ SelShared sh;
-    const int head = blockIdx.x;
-    const uint32_t *a_src = reinterpret_cast<const uint32_t *>(attn) + (size_t)head * n;
-    const uint32_t *c_src = reinterpret_cast<const uint32_t *>(crit) + (size_t)head * n;
-    uint32_t *k2 = keys2 + (size_t)head * n;
-    int32_t *out = idx + (size_t)head * max_budget;
-    const bool vec_ok = (n & 3) == 0; // every head's row then starts on a 16-byte boundary
-
-    int B = budget[head];
-    B = max(0, min(B, min(n, max_budget)));
-    const int b1 = (int)floor(alpha * (double)B);
-    const int b2 = B - b1;
-
-    // ---- stage 1: threshold of the b' largest attn ------------------------------------------------
-    uint32_t tau1 = 0u, r1 = 0u;
-    if (b1 > 0) {
-        uint32_t remaining = (uint32_t)b1, digit, above, prefix = 0u, pmask = 0u;
-        radix_hist<true>(sh, a_src, n, vec_ok, DSHIFT0, DMASK0, pmask, prefix);
-        find_digit(sh, 2048, remaining, digit, above);
-        remaining -= above; prefix |= digit << DSHIFT0; pmask |= DMASK0 << DSHIFT0;
-        radix_hist<true>(sh, a_src, n, vec_ok, DSHIFT1, DMASK1, pmask, prefix);
-        find_digit(sh, 2048, remaining, digit, above);
-        remaining -= above; prefix |= digit << DSHIFT1; pmask |= DMASK1 << DSHIFT1;
-        radix_hist<true>(sh, a_src, n, vec_ok, DSHIFT2, DMASK2, pmask, prefix);
-        find_digit(sh, 1024, remaining, digit, above);
-        remaining -= above; prefix |= digit;
-        tau1 = prefix; r1 = remaining;
+    const int slice = blockIdx.x, head = blockIdx.y;
+    int B, b1, b2;
+    head_budget(A, head, B, b1, b2);
+    const uint32_t want = STAGE == 0 ? (uint32_t)b1 : (uint32_t)b2;
+    if (want == 0) return;
+    uint32_t *hist = A.hist + ((size_t)head * 2 + STAGE) * 3 * SEL_BINS;
+    uint32_t *st = A.state + ((size_t)head * 2 + STAGE) * ST_WORDS;
+    uint32_t prefix = 0u, pmask = 0u;
+    if (PASS == 1) {
+        uint32_t d0, a0;
+        find_digit(sh, hist, 2048, want, d0, a0);
+        if (slice == 0 && threadIdx.x == 0) { st[ST_D0] = d0; st[ST_A0] = a0; }
+        prefix = d0 << DSHIFT0; pmask = DMASK0 << DSHIFT0;
+    } else if (PASS == 2) {
+        const uint32_t d0 = st[ST_D0], a0 = st[ST_A0];
+        uint32_t d1, a1;
+        find_digit(sh, hist + SEL_BINS, 2048, want - a0, d1, a1);
+        if (slice == 0 && threadIdx.x == 0) { st[ST_D1] = d1; st[ST_A1] = a1; }
+        prefix = (d0 << DSHIFT0) | (d1 << DSHIFT1);
+        pmask = (DMASK0 << DSHIFT0) | (DMASK1 << DSHIFT1);
     }
+    const int shift = PASS == 0 ? DSHIFT0 : PASS == 1 ? DSHIFT1 : 0;
+    const uint32_t mask = PASS == 2 ? DMASK2 : DMASK0;
 
-    // ---- mark stage-1 entries, write stage-2 keys, first digit histogram of stage 2 ---------------
     for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS) sh.hist[b] = 0u;
     __syncthreads();
-    uint32_t tie_seen = 0u;
-    for (int base = 0; base < n; base += SEL_PER_IT) {
-        const int i0 = base + threadIdx.x * 4;
-        uint32_t a[4], c[4];
-        load4(a_src, i0, n, vec_ok, a);
-        load4(c_src, i0, n, vec_ok, c);
-        bool gt[4], tie[4];
-        uint32_t n_tie = 0u;
+    const uint32_t *src = (STAGE == 0 ? A.attn : A.keys2) + (size_t)head * A.n;
+    const bool vec_ok = (A.n & 3) == 0;
+    const int i0 = slice * SEL_SLICE + threadIdx.x * SEL_PER_THREAD;
+    uint32_t w[8];
+    load8(src, i0, A.n, vec_ok, w);
+    // runs of equal digits inside a thread's 8 tokens are merged into one atomic
+    uint32_t run_digit = 0u, run_len = 0u;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t key = order_key(a[j]);
-            const bool valid = i0 + j < n;
-            gt[j] = b1 > 0 && valid && key > tau1;
-            tie[j] = b1 > 0 && valid && key == tau1;
-            n_tie += tie[j] ? 1u : 0u;
-        }
-        uint32_t rank = tie_seen, tot = 0u;
-        if (__syncthreads_or((int)n_tie)) rank += block_exclusive_scan(sh, n_tie, tot);
-        tie_seen += tot;
-        uint32_t key2[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            bool taken = gt[j];
-            if (tie[j]) { taken = rank < r1; ++rank; }
-            key2[j] = taken ? SEL_TAKEN : order_key(c[j]);
-            const bool on = (i0 + j < n) && !taken;
-            if (b2 > 0) hist_add(sh.hist, on, (key2[j] >> DSHIFT0) & DMASK0);
-        }
-        if (vec_ok && i0 + 3 < n) {
-            *reinterpret_cast<uint4 *>(k2 + i0) = make_uint4(key2[0], key2[1], key2[2], key2[3]);
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t key = STAGE == 0 ? order_key(w[j]) : w[j];
+        const bool on = (i0 + j < A.n) && key != SEL_TAKEN && (key & pmask) == prefix;
+        const uint32_t d = (key >> shift) & mask;
+        if (on && run_len && d == run_digit) {
+            ++run_len;
         } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (i0 + j < n) k2[i0 + j] = key2[j];
+            if (run_len) atomicAdd(&sh.hist[run_digit], run_len);
+            run_digit = d;
+            run_len = on ? 1u : 0u;
         }
     }
-    __syncthreads(); // histogram complete; keys2 written by this workgroup only and re-read after this barrier
+    if (run_len) atomicAdd(&sh.hist[run_digit], run_len);
+    __syncthreads();
+    uint32_t *dst = hist + PASS * SEL_BINS;
+    for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS) {
+        const uint32_t c = sh.hist[b];
+        if (c) atomicAdd(&dst[b], c);
+    }
+}
 
-    // ---- stage 2: threshold of the b'' largest crit among the remaining entries -------------------
-    uint32_t tau2 = 0u, r2 = 0u;
+// Decodes the last digit of a stage (tau, r) and counts, per slice, what the ordered passes need.
+//   STAGE 0: ties of stage 1 (key == tau1).
+//   STAGE 1: selected entries without ties (stage-1 members and keys > tau2) and ties of stage 2.
+template <int STAGE>
+__global__ __launch_bounds__(SEL_THREADS) void select_count_kernel(SelArgs A)
+{
+    __shared__ SelShared sh;
+    const int slice = blockIdx.x, head = blockIdx.y;
+    int B, b1, b2;
+    head_budget(A, head, B, b1, b2);
+    const uint32_t want = STAGE == 0 ? (uint32_t)b1 : (uint32_t)b2;
+    uint32_t *hist = A.hist + ((size_t)head * 2 + STAGE) * 3 * SEL_BINS;
+    uint32_t *st = A.state + ((size_t)head * 2 + STAGE) * ST_WORDS;
+    uint32_t tau = 0u, r = 0u;
+    if (want) {
+        const uint32_t d0 = st[ST_D0], a0 = st[ST_A0], d1 = st[ST_D1], a1 = st[ST_A1];
+        uint32_t d2, a2;
+        find_digit(sh, hist + 2 * SEL_BINS, 1024, want - a0 - a1, d2, a2);
+        tau = (d0 << DSHIFT0) | (d1 << DSHIFT1) | d2;
+        r = want - a0 - a1 - a2;
+    }
+    if (slice == 0 && threadIdx.x == 0) { st[ST_TAU] = tau; st[ST_R] = r; }
+
+    const uint32_t *src = (STAGE == 0 ? A.attn : A.keys2) + (size_t)head * A.n;
+    const bool vec_ok = (A.n & 3) == 0;
+    const int i0 = slice * SEL_SLICE + threadIdx.x * SEL_PER_THREAD;
+    uint32_t w[8];
+    load8(src, i0, A.n, vec_ok, w);
+    uint32_t n_tie = 0u, n_sel = 0u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t key = STAGE == 0 ? order_key(w[j]) : w[j];
+        const bool valid = i0 + j < A.n;
+        if (STAGE == 0) {
+            n_tie += (want && valid && key == tau) ? 1u : 0u;
+        } else {
+            const bool taken = valid && key == SEL_TAKEN;
+            n_sel += (taken || (want && valid && key > tau)) ? 1u : 0u;
+            n_tie += (want && valid && key == tau) ? 1u : 0u; // tau is a finite float's image, never SEL_TAKEN
+        }
+    }
+    uint32_t *sl = A.slices + (size_t)head * 3 * A.n_slices;
+    const uint32_t ties = block_sum(sh, n_tie);
+    if (STAGE == 0) {
+        if (threadIdx.x == 0) sl[slice] = ties;
+    } else {
+        const uint32_t sel = block_sum(sh, n_sel);
+        if (threadIdx.x == 0) { sl[A.n_slices + slice] = sel; sl[2 * A.n_slices + slice] = ties; }
+    }
+}
+
+// Stage-1 membership, stage-2 keys, digit-0 histogram of stage 2.
+__global__ __launch_bounds__(SEL_THREADS) void select_mark_kernel(SelArgs A)
+{
+    __shared__ SelShared sh;
+    const int slice = blockIdx.x, head = blockIdx.y;
+    int B, b1, b2;
+    head_budget(A, head, B, b1, b2);
+    const uint32_t *st1 = A.state + ((size_t)head * 2 + 0) * ST_WORDS;
+    const uint32_t tau1 = st1[ST_TAU], r1 = st1[ST_R];
+    const uint32_t *sl = A.slices + (size_t)head * 3 * A.n_slices;
+    // ties of stage 1 in earlier slices
+    uint32_t before = 0u;
+    for (int s = threadIdx.x; s < slice; s += SEL_THREADS) before += sl[s];
+    before = block_sum(sh, before);
+
+    const bool vec_ok = (A.n & 3) == 0;
+    const int i0 = slice * SEL_SLICE + threadIdx.x * SEL_PER_THREAD;
+    uint32_t a[8], c[8];
+    load8(A.attn + (size_t)head * A.n, i0, A.n, vec_ok, a);
+    load8(A.crit + (size_t)head * A.n, i0, A.n, vec_ok, c);
+    bool gt[8], tie[8];
+    uint32_t n_tie = 0u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t key = order_key(a[j]);
+        const bool valid = i0 + j < A.n;
+        gt[j] = b1 > 0 && valid && key > tau1;
+        tie[j] = b1 > 0 && valid && key == tau1;
+        n_tie += tie[j] ? 1u : 0u;
+    }
+    uint32_t tot;
+    uint32_t rank = before + block_exclusive_scan(sh, n_tie, tot);
+    for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS) sh.hist[b] = 0u;
+    __syncthreads();
+    uint32_t key2[8];
+    uint32_t run_digit = 0u, run_len = 0u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        bool taken = gt[j];
+        if (tie[j]) { taken = rank < r1; ++rank; }
+        key2[j] = taken ? SEL_TAKEN : order_key(c[j]);
+        const bool on = b2 > 0 && (i0 + j < A.n) && !taken;
+        const uint32_t d = (key2[j] >> DSHIFT0) & DMASK0;
+        if (on && run_len && d == run_digit) {
+            ++run_len;
+        } else {
+            if (run_len) atomicAdd(&sh.hist[run_digit], run_len);
+            run_digit = d;
+            run_len = on ? 1u : 0u;
+        }
+    }
+    if (run_len) atomicAdd(&sh.hist[run_digit], run_len);
+    uint32_t *k2 = A.keys2 + (size_t)head * A.n;
+    if (vec_ok && i0 + 7 < A.n) {
+        *reinterpret_cast<uint4 *>(k2 + i0) = make_uint4(key2[0], key2[1], key2[2], key2[3]);
+        *reinterpret_cast<uint4 *>(k2 + i0 + 4) = make_uint4(key2[4], key2[5], key2[6], key2[7]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (i0 + j < A.n) k2[i0 + j] = key2[j];
+    }
+    __syncthreads();
     if (b2 > 0) {
-        uint32_t remaining = (uint32_t)b2, digit, above, prefix = 0u, pmask = 0u;
-        find_digit(sh, 2048, remaining, digit, above);
-        remaining -= above; prefix |= digit << DSHIFT0; pmask |= DMASK0 << DSHIFT0;
-        radix_hist<false>(sh, k2, n, vec_ok, DSHIFT1, DMASK1, pmask, prefix);
-        find_digit(sh, 2048, remaining, digit, above);
-        remaining -= above; prefix |= digit << DSHIFT1; pmask |= DMASK1 << DSHIFT1;
-        radix_hist<false>(sh, k2, n, vec_ok, DSHIFT2, DMASK2, pmask, prefix);
-        find_digit(sh, 1024, remaining, digit, above);
-        remaining -= above; prefix |= digit;
-        tau2 = prefix; r2 = remaining;
+        uint32_t *dst = A.hist + ((size_t)head * 2 + 1) * 3 * SEL_BINS;
+        for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS) {
+            const uint32_t cnt = sh.hist[b];
+            if (cnt) atomicAdd(&dst[b], cnt);
+        }
     }
+}
 
-    // ---- ordered write of S1 u S2 ------------------------------------------------------------------
-    uint32_t out_base = 0u;
-    tie_seen = 0u;
-    for (int base = 0; base < n; base += SEL_PER_IT) {
-        const int i0 = base + threadIdx.x * 4;
-        uint32_t key[4];
-        load4(k2, i0, n, vec_ok, key);
-        bool sel[4], tie[4];
-        uint32_t n_tie = 0u;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool valid = i0 + j < n;
-            const bool taken = valid && key[j] == SEL_TAKEN;
-            sel[j] = taken || (b2 > 0 && valid && key[j] > tau2);
-            tie[j] = b2 > 0 && valid && key[j] == tau2; // tau2 is a finite float's image, never SEL_TAKEN
-            n_tie += tie[j] ? 1u : 0u;
-        }
-        uint32_t rank = tie_seen, tot = 0u;
-        if (__syncthreads_or((int)n_tie)) rank += block_exclusive_scan(sh, n_tie, tot);
-        tie_seen += tot;
-        uint32_t n_sel = 0u;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (tie[j]) { sel[j] = rank < r2; ++rank; }
-            n_sel += sel[j] ? 1u : 0u;
-        }
-        uint32_t tot_sel;
-        uint32_t pos = out_base + block_exclusive_scan(sh, n_sel, tot_sel);
-        out_base += tot_sel;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (sel[j]) {
-                if (pos < (uint32_t)max_budget) out[pos] = i0 + j;
-                ++pos;
-            }
+// Ordered write of S1 u S2.
+__global__ __launch_bounds__(SEL_THREADS) void select_write_kernel(SelArgs A)
+{
+    __shared__ SelShared sh;
+    const int slice = blockIdx.x, head = blockIdx.y;
+    int B, b1, b2;
+    head_budget(A, head, B, b1, b2);
+    const uint32_t *st2 = A.state + ((size_t)head * 2 + 1) * ST_WORDS;
+    const uint32_t tau2 = st2[ST_TAU], r2 = st2[ST_R];
+    const uint32_t *sel_cnt = A.slices + (size_t)head * 3 * A.n_slices + A.n_slices;
+    const uint32_t *tie_cnt = sel_cnt + A.n_slices;
+    // entries written and stage-2 ties seen by earlier slices: slice s' contributes
+    // sel_cnt[s'] + clamp(r2 - ties before s', 0, tie_cnt[s'])
+    uint32_t out_base = 0u, tie_base = 0u, carry = 0u;
+    for (int c0 = 0; c0 < slice; c0 += SEL_THREADS) {
+        const int s = c0 + threadIdx.x;
+        const uint32_t t = s < slice ? tie_cnt[s] : 0u;
+        uint32_t tot;
+        const uint32_t tb = carry + block_exclusive_scan(sh, t, tot);
+        uint32_t mine = 0u;
+        if (s < slice) mine = sel_cnt[s] + min(r2 > tb ? r2 - tb : 0u, t);
+        out_base += block_sum(sh, mine);
+        carry += tot;
     }
-    for (int j = B + (int)threadIdx.x; j < max_budget; j += SEL_THREADS) out[j] = -1;
-    if (threadIdx.x == 0) count[head] = B;
+    tie_base = carry;
+
+    const bool vec_ok = (A.n & 3) == 0;
+    const int i0 = slice * SEL_SLICE + threadIdx.x * SEL_PER_THREAD;
+    uint32_t key[8];
+    load8(A.keys2 + (size_t)head * A.n, i0, A.n, vec_ok, key);
+    bool sel[8], tie[8];
+    uint32_t n_tie = 0u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const bool valid = i0 + j < A.n;
+        const bool taken = valid && key[j] == SEL_TAKEN;
+        sel[j] = taken || (b2 > 0 && valid && key[j] > tau2);
+        tie[j] = b2 > 0 && valid && key[j] == tau2;
+        n_tie += tie[j] ? 1u : 0u;
+    }
+    uint32_t tot;
+    uint32_t rank = tie_base + block_exclusive_scan(sh, n_tie, tot);
+    uint32_t n_sel = 0u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        if (tie[j]) { sel[j] = rank < r2; ++rank; }
+        n_sel += sel[j] ? 1u : 0u;
+    }
+    uint32_t pos = out_base + block_exclusive_scan(sh, n_sel, tot);
+    int32_t *out = A.idx + (size_t)head * A.max_budget;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (sel[j]) {
+            if (pos < (uint32_t)A.max_budget) out[pos] = i0 + j;
+            ++pos;
+        }
+    // unused tail and the count, spread over the slices
+    for (int j = B + slice * SEL_THREADS + (int)threadIdx.x; j < A.max_budget; j += A.n_slices * SEL_THREADS) out[j] = -1;
+    if (slice == 0 && threadIdx.x == 0) A.count[head] = B;
+}
+
+size_t select_workspace_words(int heads, int n)
+{
+    const size_t n_slices = (size_t)(n + SEL_SLICE - 1) / SEL_SLICE;
+    return (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS) + (size_t)heads * 3 * n_slices;
 }
 
 hipError_t launch_select(const Dims &d, const float *attn, const float *crit, const int32_t *budget, float alpha,
-                         int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2, hipStream_t s)
+                         int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2, uint32_t *scratch,
+                         hipStream_t s)
 {
-    hipLaunchKernelGGL(select_kernel, dim3(d.batch * d.Hkv), dim3(SEL_THREADS), 0, s, attn, crit, budget, (double)alpha,
-                       d.n, max_budget, idx, count, keys2);
+    const int heads = d.batch * d.Hkv;
+    SelArgs A;
+    A.attn = reinterpret_cast<const uint32_t *>(attn);
+    A.crit = reinterpret_cast<const uint32_t *>(crit);
+    A.budget = budget;
+    A.keys2 = keys2;
+    A.hist = scratch;
+    A.state = scratch + (size_t)heads * 2 * 3 * SEL_BINS;
+    A.slices = A.state + (size_t)heads * 2 * ST_WORDS;
+    A.idx = idx; A.count = count;
+    A.alpha = (double)alpha;
+    A.n = d.n; A.max_budget = max_budget;
+    A.n_slices = (d.n + SEL_SLICE - 1) / SEL_SLICE;
+    const size_t zero_words = (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS);
+    dim3 grid(A.n_slices, heads), block(SEL_THREADS);
+    hipLaunchKernelGGL(select_zero_kernel, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, s, scratch, zero_words);
+    hipLaunchKernelGGL((select_hist_kernel<0, 0>), grid, block, 0, s, A);
+    hipLaunchKernelGGL((select_hist_kernel<0, 1>), grid, block, 0, s, A);
+    hipLaunchKernelGGL((select_hist_kernel<0, 2>), grid, block, 0, s, A);
+    hipLaunchKernelGGL(select_count_kernel<0>, grid, block, 0, s, A);
+    hipLaunchKernelGGL(select_mark_kernel, grid, block, 0, s, A);
+    hipLaunchKernelGGL((select_hist_kernel<1, 1>), grid, block, 0, s, A);
+    hipLaunchKernelGGL((select_hist_kernel<1, 2>), grid, block, 0, s, A);
+    hipLaunchKernelGGL(select_count_kernel<1>, grid, block, 0, s, A);
+    hipLaunchKernelGGL(select_write_kernel, grid, block, 0, s, A);
     return hipGetLastError();
 }
 
