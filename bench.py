@@ -98,7 +98,8 @@ def main():
     sets = []
     host0 = None
     for s in range(nsets):
-        t = make_layer(cfg, layer=0, seed_offset=s)
+        # multi-layer workloads rotate the inputs of different layers, single layers rotate seed offsets
+        t = make_layer(cfg, layer=s, seed_offset=0) if cfg.n_layers > 1 else make_layer(cfg, layer=0, seed_offset=s)
         if s == 0:
             host0 = t
         dev = to_device(cfg, t, True)
@@ -196,7 +197,9 @@ def main():
         "config": {"workload": f"{cfg.name}: batch {b}, {H} q / {Hkv} kv heads, d_h {dh}, d_model {dm}, n {n}, "
                                f"W {cfg.window}, pool {cfg.pool_kernel}, budget {B}/head, alpha {cfg.alpha}",
                    "w_o_layout": "[d_model, H*d_h] (CKV_WO_OUT_IN)", "input_sets_rotated": nsets,
-                   "tokens_per_s": round(b * n / (ms_per_step * 1e-3), 1)},
+                   "tokens_per_s": round(b * n / (ms_per_step * 1e-3), 1),
+                   **({"layers": cfg.n_layers, "total_ms_all_layers": round(cfg.n_layers * ms_per_step, 3)}
+                      if cfg.n_layers > 1 else {})},
         "roofline": {"kernel": "vproj_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": None, "avg_launch_ms": round(vproj_avg, 4),

@@ -225,31 +225,61 @@ def test_budget_is_clamped_to_n_and_max_budget(P):
 
 
 # ------------------------------------------------------------------------------------------------ full-size
-@pytest.mark.parametrize("name", ["llama32k"])
-def test_full_size_sampled(P, name):
+def _full_size_check(P, cfg, t, sweeps=None, layer_label=""):
     """Full BASELINE shape in the launch configuration the benchmark times (output-major W_O).
     attn is checked in full (the oracle's window attention is cheap); the projected norm and the
     criticality on sampled tokens; the selection must equal the oracle's selection on the GPU's own
-    float32 keys exactly; compaction bit-exact."""
-    cfg = CONFIGS[name]
-    t = make_layer(cfg)
+    float32 keys exactly (for every (budget, alpha) of the sweep); compaction bit-exact."""
+    import torch
     res = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, wo_out_in=True)
     a = O.window_attention(t["q_win"], t["k"])
     abar = O.maxpool1d(a, cfg.pool_kernel)
     r = np.random.Generator(np.random.PCG64(123))
     rows = np.unique(np.concatenate([r.integers(0, cfg.n_ctx, 384), [0, 1, 2, 3, cfg.n_ctx - 1, cfg.n_ctx - 2]]))
     N_s = O.projected_value_norm(t["v"][:, :, rows], t["w_o"], cfg.n_q_heads)
-    attn_s, crit_s = O.group_keys(abar[:, :, rows], N_s, cfg.n_kv_heads, cfg.eps)
+    _, crit_s = O.group_keys(abar[:, :, rows], N_s, cfg.n_kv_heads, cfg.eps)
     attn_full, _ = O.group_keys(abar, np.zeros_like(abar), cfg.n_kv_heads, cfg.eps)
     e_a = assert_scores_close(res.attn, attn_full, "attn (all tokens)")
     e_v = assert_scores_close(res.vnorm[:, :, rows], N_s, "vnorm (sampled tokens)")
-    # the error floor uses the global maximum of the oracle quantity; sampled maxima serve for crit
     e_c = assert_scores_close(res.crit[:, :, rows], crit_s, "crit (sampled tokens)")
     ref_idx, ref_count, _ = O.select(res.attn.astype(np.float64), res.crit.astype(np.float64), cfg.budget,
                                      np.float32(cfg.alpha))
     assert np.array_equal(res.count, ref_count) and np.array_equal(res.idx, ref_idx)
     assert_compaction_exact(res, t, cfg.budget)
-    print(f"[{name} full] max rel err attn {e_a[0]:.2e} vnorm {e_v[0]:.2e} crit {e_c[0]:.2e} on {rows.size} sampled tokens")
+    # the two-stage result must differ from attention-only Top-B on this workload (stage 2 is exercised)
+    top_idx, _, _ = O.select(res.attn.astype(np.float64), res.crit.astype(np.float64), cfg.budget, 1.0)
+    assert not np.array_equal(top_idx, ref_idx)
+    print(f"[{cfg.name}{layer_label} full] max rel err attn {e_a[0]:.2e} vnorm {e_v[0]:.2e} crit {e_c[0]:.2e} "
+          f"on {rows.size} sampled tokens; selection exact on {cfg.batch * cfg.n_kv_heads} heads")
+    for B, alpha in (sweeps or []):
+        idx, count, _ = run_select(P, res.attn, res.crit, B, alpha)
+        ref_idx, ref_count, _ = O.select(res.attn.astype(np.float64), res.crit.astype(np.float64), B, np.float32(alpha))
+        assert np.array_equal(count, ref_count) and np.array_equal(idx, ref_idx), (B, alpha)
+    del res
+    torch.cuda.empty_cache()
+
+
+def test_full_size_llama32k(P):
+    cfg = CONFIGS["llama32k"]
+    _full_size_check(P, cfg, make_layer(cfg))
+
+
+def test_full_size_llama128k(P):
+    cfg = CONFIGS["llama128k"]
+    _full_size_check(P, cfg, make_layer(cfg))
+
+
+def test_full_size_qwen128k_with_budget_and_alpha_sweep(P):
+    cfg = CONFIGS["qwen128k"]
+    sweeps = [(B, a) for B in (13107, 26214, 52429) for a in (0.25, 0.5, 0.75)]
+    _full_size_check(P, cfg, make_layer(cfg), sweeps=sweeps)
+
+
+@pytest.mark.parametrize("layer", [0, 31])
+def test_full_size_mistral_prefill_layer(P, layer):
+    """One layer of the 32-layer batch-4 prefill workload (independent seeds per layer)."""
+    cfg = CONFIGS["mistral_prefill"]
+    _full_size_check(P, cfg, make_layer(cfg, layer=layer), layer_label=f" layer {layer}")
 
 
 # ------------------------------------------------------------------------------------------------ runtime plumbing
