@@ -22,6 +22,10 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# HBM-side bytes per launch of the projection kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00 after calibration against a 1 GiB device copy); the runs and the
+# calibration are written up in profiles/whole_pass_llama32k_hbm_counters.md.  None where not measured.
+VPROJ_TRAFFIC_BYTES = {"llama32k": int((328.9 + 4.0) * 2**20)}
 
 
 class HipEvents:
@@ -202,7 +206,7 @@ def main():
                       if cfg.n_layers > 1 else {})},
         "roofline": {"kernel": "vproj_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None, "avg_launch_ms": round(vproj_avg, 4),
+                     "traffic": VPROJ_TRAFFIC_BYTES.get(cfg.name), "avg_launch_ms": round(vproj_avg, 4),
                      "algorithmic_flop_per_launch": flops},
         "stages_ms": stage_ms,
         "pass_lower_bound_ms": round(t_bound_ms, 4), "pass_frac_of_bound": round(t_bound_ms / ms_per_step, 4),

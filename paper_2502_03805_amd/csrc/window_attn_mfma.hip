@@ -28,7 +28,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int AM_DH = 128;
 constexpr int AM_TILE_KEYS = 64;
 constexpr int AM_TILE_BYTES = AM_TILE_KEYS * AM_DH * 2; // 16 KiB
-constexpr int AM_CHUNK = 512;                           // keys per workgroup
+constexpr int AM_CHUNK = 256;                           // keys per workgroup
 constexpr int AM_MAX_WAVES = 8;
 constexpr float AM_LOG2E = 1.4426950408889634f;
 constexpr float AM_NEG = -1.0e30f;
@@ -64,15 +64,22 @@ __device__ __forceinline__ void load_q_frags(const AttnArgs &A, int bi, int head
 // Direct global->LDS load of one 64-key tile, shared among the nw waves of the workgroup.
 // Instruction j fills LDS KiB j = keys 4j .. 4j+3; lane i writes slot i % 16 of key 4j + i / 16 and
 // fetches 16-byte chunk (i % 16) ^ (key & 15) of that key row.  Rows past n-1 re-read row n-1.
-__device__ __forceinline__ void load_k_tile(const bf16_t *kbase, int64_t ks2, int key0, int n, char *buf, int wave,
-                                            int nw, int lane)
+// The loads are buffer loads (not flat/global ones) so that the compiler keeps exact LDS wait counts.
+__device__ __forceinline__ void load_k_tile(__amdgpu_buffer_rsrc_t krsrc, int64_t ks2, int key0, int n, char *buf,
+                                            int wave, int nw, int lane)
 {
     for (int j = wave; j < AM_TILE_BYTES / 1024; j += nw) {
         const int key_in_tile = 4 * j + (lane >> 4);
         const int key = min(key0 + key_in_tile, n - 1);
-        const bf16_t *src = kbase + (int64_t)key * ks2 + (((lane & 15) ^ (key_in_tile & 15)) * 8);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(buf + j * 1024), 16, 0, 0);
+        const uint32_t voff = (uint32_t)(((int64_t)key * ks2 + (((lane & 15) ^ (key_in_tile & 15)) * 8)) * 2);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, LDS_PTR(buf + j * 1024), 16, voff, 0, 0, 0);
     }
+}
+
+// Buffer descriptor over one kv head's keys (token stride ks2 elements; the host checks n * ks2 * 2 < 2 GiB).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_k_rsrc(const bf16_t *kbase, int64_t ks2, int n)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)kbase, 0, (int)(((int64_t)(n - 1) * ks2 + AM_DH) * 2), 0x00020000);
 }
 
 __device__ __forceinline__ void read_k_frags(const char *tile, int kb, int l32, int half, bf16x8 (&kf)[8])
@@ -94,11 +101,12 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_stats_mfma_kernel(Attn
     __shared__ __attribute__((aligned(1024))) char lds[2 * AM_TILE_BYTES];
     const int chunk = blockIdx.x, bi = blockIdx.y / (A.H / A.G), g = blockIdx.y % (A.H / A.G);
     const int nw = blockDim.x >> 6;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int head = g * A.G + blockIdx.z * AM_MAX_WAVES + wave;       // query head of this wave
     const bool head_ok = blockIdx.z * AM_MAX_WAVES + wave < A.G;
     const bf16_t *kbase = A.k + bi * A.ks0 + g * A.ks1;
+    const __amdgpu_buffer_rsrc_t krsrc = make_k_rsrc(kbase, A.ks2, A.n);
     const int key_begin = chunk * AM_CHUNK;
     const int key_end = min(key_begin + AM_CHUNK, A.n);
     const int tiles = (key_end - key_begin + AM_TILE_KEYS - 1) / AM_TILE_KEYS;
@@ -109,12 +117,12 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_stats_mfma_kernel(Attn
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) { m[qb] = AM_NEG; l[qb] = 0.f; }
 
-    load_k_tile(kbase, A.ks2, key_begin, A.n, lds, wave, nw, lane);
+    load_k_tile(krsrc, A.ks2, key_begin, A.n, lds, wave, nw, lane);
     __syncthreads();
     for (int t = 0; t < tiles; ++t) {
         const char *cur = lds + (t & 1) * AM_TILE_BYTES;
         if (t + 1 < tiles)
-            load_k_tile(kbase, A.ks2, key_begin + (t + 1) * AM_TILE_KEYS, A.n, lds + ((t + 1) & 1) * AM_TILE_BYTES, wave,
+            load_k_tile(krsrc, A.ks2, key_begin + (t + 1) * AM_TILE_KEYS, A.n, lds + ((t + 1) & 1) * AM_TILE_BYTES, wave,
                         nw, lane);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
@@ -129,18 +137,20 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_stats_mfma_kernel(Attn
 #pragma unroll
                 for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[qb][s], acc, 0, 0, 0);
                 // acc[j]: key key0 + 8*(j/4) + 4*half + j%4, query row l32
-                float tv[16];
-                float tmax = AM_NEG;
+                // t = acc * c with c > 0, so the block maximum of t is c * max(acc); 2^(t - m) = 2^fma(acc, c, -m)
+                if (ragged) {
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    tv[j] = acc[j] * A.c;
-                    if (ragged && key0 + 8 * (j / 4) + 4 * half + (j % 4) >= A.n) tv[j] = -INFINITY;
-                    tmax = fmaxf(tmax, tv[j]);
+                    for (int j = 0; j < 16; ++j)
+                        if (key0 + 8 * (j / 4) + 4 * half + (j % 4) >= A.n) acc[j] = -INFINITY;
                 }
-                const float mn = fmaxf(m[qb], tmax);
+                float amax = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
+#pragma unroll
+                for (int j = 3; j < 15; j += 2) amax = fmaxf(fmaxf(amax, acc[j]), acc[j + 1]);
+                amax = fmaxf(amax, acc[15]);
+                const float mn = fmaxf(m[qb], amax * A.c);
                 float add = 0.f;
 #pragma unroll
-                for (int j = 0; j < 16; ++j) add += __builtin_amdgcn_exp2f(tv[j] - mn);
+                for (int j = 0; j < 16; ++j) add += __builtin_amdgcn_exp2f(fmaf(acc[j], A.c, -mn));
                 l[qb] = l[qb] * __builtin_amdgcn_exp2f(m[qb] - mn) + add;
                 m[qb] = mn;
             }
@@ -190,11 +200,12 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_colsum_mfma_kernel(Att
     __shared__ __attribute__((aligned(1024))) char lds[2 * AM_TILE_BYTES];
     const int chunk = blockIdx.x, bi = blockIdx.y / (A.H / A.G), g = blockIdx.y % (A.H / A.G);
     const int nw = blockDim.x >> 6;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int head = g * A.G + blockIdx.z * AM_MAX_WAVES + wave;
     const bool head_ok = blockIdx.z * AM_MAX_WAVES + wave < A.G;
     const bf16_t *kbase = A.k + bi * A.ks0 + g * A.ks1;
+    const __amdgpu_buffer_rsrc_t krsrc = make_k_rsrc(kbase, A.ks2, A.n);
     const int key_begin = chunk * AM_CHUNK;
     const int key_end = min(key_begin + AM_CHUNK, A.n);
     const int tiles = (key_end - key_begin + AM_TILE_KEYS - 1) / AM_TILE_KEYS;
@@ -212,12 +223,12 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_colsum_mfma_kernel(Att
         }
     float *out = a_raw + ((size_t)bi * A.H + (head_ok ? head : g * A.G)) * (size_t)A.n;
 
-    load_k_tile(kbase, A.ks2, key_begin, A.n, lds, wave, nw, lane);
+    load_k_tile(krsrc, A.ks2, key_begin, A.n, lds, wave, nw, lane);
     __syncthreads();
     for (int t = 0; t < tiles; ++t) {
         const char *cur = lds + (t & 1) * AM_TILE_BYTES;
         if (t + 1 < tiles)
-            load_k_tile(kbase, A.ks2, key_begin + (t + 1) * AM_TILE_KEYS, A.n, lds + ((t + 1) & 1) * AM_TILE_BYTES, wave,
+            load_k_tile(krsrc, A.ks2, key_begin + (t + 1) * AM_TILE_KEYS, A.n, lds + ((t + 1) & 1) * AM_TILE_BYTES, wave,
                         nw, lane);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
@@ -243,7 +254,10 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_colsum_mfma_kernel(Att
     }
 }
 
-bool attn_mfma_supported(const Dims &d) { return d.dh == AM_DH && d.W <= 96; }
+bool attn_mfma_supported(const Dims &d)
+{
+    return d.dh == AM_DH && d.W <= 96 && ((int64_t)(d.n - 1) * d.ks[2] + AM_DH) * 2 < ((int64_t)1 << 31);
+}
 int mfma_attn_chunks(const Dims &d) { return (d.n + AM_CHUNK - 1) / AM_CHUNK; }
 
 static AttnArgs make_args(const Dims &d, const void *q, const void *k, int chunks)
