@@ -181,7 +181,7 @@ bool vproj_mfma_supported(const Dims &d)
 
 hipError_t launch_vproj_mfma(const Dims &d, const void *v, const void *w_t, float *vnorm, hipStream_t s)
 {
-    constexpr int RB = 4;
+    constexpr int RB = 6;
     const int rows_per_wg = VM_WAVES * RB * 16;
     dim3 grid((d.n + rows_per_wg - 1) / rows_per_wg, d.H, d.batch);
     hipLaunchKernelGGL((vproj_mfma_kernel<RB>), grid, dim3(VM_THREADS), 0, s, (const bf16_t *)v, (const bf16_t *)w_t,
