@@ -74,6 +74,8 @@ def main():
     ap.add_argument("--sets", type=int, default=0, help="independent input sets rotated over the steps (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=12288)
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams the steps are issued on round-robin (independent layers overlap); 1 = serial")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale profiler byte counters)")
     args = ap.parse_args()
@@ -98,7 +100,6 @@ def main():
     nsets = args.sets or max(2, min(4, int(np.ceil(512e6 / kv_bytes))))
     desc = cfg_desc(P, cfg, flags=P.CKV_WO_OUT_IN)
     B = cfg.budget
-    ws = torch.empty(P.workspace_bytes(desc, B), dtype=torch.uint8, device="cuda")
     sets = []
     host0 = None
     for s in range(nsets):
@@ -110,23 +111,40 @@ def main():
         if s > 0:
             dev["w_o"] = sets[0]["w_o"]  # the projection is a weight: one copy
         sets.append(dev)
-    attn = torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda")
-    crit = torch.empty_like(attn)
-    idx = torch.empty((b, Hkv, B), dtype=torch.int32, device="cuda")
-    count = torch.empty((b, Hkv), dtype=torch.int32, device="cuda")
-    k_out = torch.empty((b, Hkv, B, dh), dtype=sets[0]["k"].dtype, device="cuda")
-    v_out = torch.empty_like(k_out)
     budget = torch.full((b, Hkv), B, dtype=torch.int32, device="cuda")
-    stream = torch.cuda.current_stream()
-    sh = stream.cuda_stream or None
+    # Steps are independent layers; they are issued round-robin on `--streams` streams (each with its own
+    # workspace and outputs).  The score calls are chained with events (one projection kernel at a time),
+    # so what overlaps is the light selection / gather tail of one layer with the scoring of the next.
+    # All default-priority streams.
+    n_streams = max(1, args.streams)
+    lanes = []
+    for _ in range(n_streams):
+        lanes.append(dict(
+            stream=torch.cuda.Stream(),
+            ws=torch.empty(P.workspace_bytes(desc, B), dtype=torch.uint8, device="cuda"),
+            attn=torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda"),
+            crit=torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda"),
+            idx=torch.empty((b, Hkv, B), dtype=torch.int32, device="cuda"),
+            count=torch.empty((b, Hkv), dtype=torch.int32, device="cuda"),
+            k_out=torch.empty((b, Hkv, B, dh), dtype=sets[0]["k"].dtype, device="cuda"),
+            v_out=torch.empty((b, Hkv, B, dh), dtype=sets[0]["k"].dtype, device="cuda")))
     ev = HipEvents(P.hip_runtime())
     n_slots = 2 * len(P.STAGES)
 
-    def one_pass(dev, stage_events):
-        P.criticalkv_score_profiled(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], attn, crit, None,
-                                    workspace=ws, stage_events=stage_events, stream=stream)
-        P.criticalkv_select(desc, attn, crit, budget, cfg.alpha, B, idx, count, workspace=ws, stream=stream)
-        P.criticalkv_compact(desc, dev["k"], dev["v"], idx, count, B, k_out, v_out, stream=stream)
+    score_done = [None]  # event after the latest score: scores are chained, only the light tail overlaps
+
+    def one_pass(dev, lane, stage_events):
+        st = lane["stream"]
+        if n_streams > 1 and score_done[0] is not None:
+            st.wait_event(score_done[0])
+        P.criticalkv_score_profiled(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], lane["attn"], lane["crit"], None,
+                                    workspace=lane["ws"], stage_events=stage_events, stream=st)
+        if n_streams > 1:
+            score_done[0] = torch.cuda.Event()
+            score_done[0].record(st)
+        P.criticalkv_select(desc, lane["attn"], lane["crit"], budget, cfg.alpha, B, lane["idx"], lane["count"],
+                            workspace=lane["ws"], stream=st)
+        P.criticalkv_compact(desc, dev["k"], dev["v"], lane["idx"], lane["count"], B, lane["k_out"], lane["v_out"], stream=st)
 
     if args.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -136,8 +154,9 @@ def main():
         del src, dst
 
     none_events = (ctypes.c_void_p * n_slots)()
+    torch.cuda.synchronize()
     for w in range(args.warmup):
-        one_pass(sets[w % nsets], none_events)
+        one_pass(sets[w % nsets], lanes[w % n_streams], none_events)
     torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps; only the dominant kernel carries event marks --------------------
@@ -150,29 +169,41 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        one_pass(sets[s % nsets], step_events[s])
+        one_pass(sets[s % nsets], lanes[s % n_streams], step_events[s])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     vproj_ms = [ev.ms(ctypes.c_void_p(a[vslot]), ctypes.c_void_p(a[vslot + 1])) for a in step_events]
     vproj_avg = float(np.mean(vproj_ms))
-    assert int(count.min()) == B and int(count.max()) == B
+    for lane in lanes[:min(n_streams, args.steps)]:
+        assert int(lane["count"].min()) == B and int(lane["count"].max()) == B
 
-    # ---- untimed extra passes: per-stage breakdown -------------------------------------------------------
+    # ---- untimed extras: the same K steps on one stream, and a per-stage breakdown -----------------------
+    lane0 = lanes[0]
+    torch.cuda.synchronize()
+    s0 = time.perf_counter()
+    for s in range(args.steps):
+        one_pass(sets[s % nsets], lane0, none_events)
+    torch.cuda.synchronize()
+    serial_ms_per_step = (time.perf_counter() - s0) * 1e3 / args.steps
     stage_ms = {name: [] for name in P.STAGES}
     stage_ms["select"], stage_ms["compact"] = [], []
+    stream = lane0["stream"]
+    sh = stream.cuda_stream or None
     for s in range(min(5, max(2, args.steps))):
         dev = sets[s % nsets]
         arr = (ctypes.c_void_p * n_slots)()
         for j in range(n_slots):
             arr[j] = ev.new()
         e_sel0, e_sel1, e_cp1 = ev.new(), ev.new(), ev.new()
-        P.criticalkv_score_profiled(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], attn, crit, None,
-                                    workspace=ws, stage_events=arr, stream=stream)
+        P.criticalkv_score_profiled(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], lane0["attn"], lane0["crit"], None,
+                                    workspace=lane0["ws"], stage_events=arr, stream=stream)
         ev.record(e_sel0, sh)
-        P.criticalkv_select(desc, attn, crit, budget, cfg.alpha, B, idx, count, workspace=ws, stream=stream)
+        P.criticalkv_select(desc, lane0["attn"], lane0["crit"], budget, cfg.alpha, B, lane0["idx"], lane0["count"],
+                            workspace=lane0["ws"], stream=stream)
         ev.record(e_sel1, sh)
-        P.criticalkv_compact(desc, dev["k"], dev["v"], idx, count, B, k_out, v_out, stream=stream)
+        P.criticalkv_compact(desc, dev["k"], dev["v"], lane0["idx"], lane0["count"], B, lane0["k_out"], lane0["v_out"],
+                             stream=stream)
         ev.record(e_cp1, sh)
         torch.cuda.synchronize()
         for i, name in enumerate(P.STAGES):
@@ -201,6 +232,7 @@ def main():
         "config": {"workload": f"{cfg.name}: batch {b}, {H} q / {Hkv} kv heads, d_h {dh}, d_model {dm}, n {n}, "
                                f"W {cfg.window}, pool {cfg.pool_kernel}, budget {B}/head, alpha {cfg.alpha}",
                    "w_o_layout": "[d_model, H*d_h] (CKV_WO_OUT_IN)", "input_sets_rotated": nsets,
+                   "streams": n_streams, "serial_ms_per_step": round(serial_ms_per_step, 4),
                    "tokens_per_s": round(b * n / (ms_per_step * 1e-3), 1),
                    **({"layers": cfg.n_layers, "total_ms_all_layers": round(cfg.n_layers * ms_per_step, 3)}
                       if cfg.n_layers > 1 else {})},

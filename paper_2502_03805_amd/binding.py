@@ -12,7 +12,8 @@ from dataclasses import dataclass
 from typing import Optional
 
 PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(PKG, "libcriticalkv.so")
+# CRITICALKV_LIB overrides the library file (to compare two builds in one process-per-build run)
+LIB_PATH = os.environ.get("CRITICALKV_LIB") or os.path.join(PKG, "libcriticalkv.so")
 
 CKV_BF16, CKV_F32 = 0, 1
 CKV_NORM_L1 = 1

@@ -47,15 +47,25 @@ template <int RB>
 __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t *__restrict__ v,
                                                                    const bf16_t *__restrict__ w_t,
                                                                    float *__restrict__ vnorm, int H, int G, int n,
-                                                                   int dm, int64_t vs0, int64_t vs1, int64_t vs2)
+                                                                   int dm, int64_t vs0, int64_t vs1, int64_t vs2,
+                                                                   int row_tiles, int heads)
 {
     static_assert(VM_LOADS == VM_CB, "one direct load per wave and column block");
     __shared__ __attribute__((aligned(1024))) char lds[2 * VM_TILE_BYTES];
-    const int h = blockIdx.y, bi = blockIdx.z, g = h / G;
+    // XCD-aware work mapping.  Workgroups of a 1-D grid are handed to the 8 XCDs round-robin (workgroup L
+    // runs on XCD L % 8) and every XCD has its own 4 MiB L2.  Each (batch item, query head) is pinned to
+    // one XCD, which walks its heads one after the other with the row tile running fastest: the
+    // workgroups resident on an XCD then stream the same 1 MiB W_O slice (or two of them), which stays in
+    // that L2 instead of several slices evicting each other.
+    const int xcd = blockIdx.x & 7, k_in_xcd = blockIdx.x >> 3;
+    const int hb = xcd + 8 * (k_in_xcd / row_tiles); // batch * H + head
+    if (hb >= heads) return;
+    const int tile_x = k_in_xcd % row_tiles;
+    const int h = hb % H, bi = hb / H, g = h / G;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform, kept in a scalar register
     const int l16 = lane & 15, kc = lane >> 4;
-    const int row0 = (blockIdx.x * VM_WAVES + wave) * (RB * 16);
+    const int row0 = (tile_x * VM_WAVES + wave) * (RB * 16);
 
     // A fragments: rows of V, resident in registers
     bf16x8 a[RB][VM_KS];
@@ -176,16 +186,19 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
 
 bool vproj_mfma_supported(const Dims &d)
 {
-    return d.dh == VM_DH && d.dm % VM_TN == 0 && (size_t)d.dm * d.H * d.dh * 2 < ((size_t)1 << 31);
+    return d.dh == VM_DH && d.dm % VM_TN == 0 && (size_t)d.dm * d.H * d.dh * 2 < ((size_t)1 << 31) &&
+           ((long long)d.batch * d.H + 8) * (d.n / 64 + 2) < (1ll << 31);
 }
 
 hipError_t launch_vproj_mfma(const Dims &d, const void *v, const void *w_t, float *vnorm, hipStream_t s)
 {
     constexpr int RB = 6;
     const int rows_per_wg = VM_WAVES * RB * 16;
-    dim3 grid((d.n + rows_per_wg - 1) / rows_per_wg, d.H, d.batch);
-    hipLaunchKernelGGL((vproj_mfma_kernel<RB>), grid, dim3(VM_THREADS), 0, s, (const bf16_t *)v, (const bf16_t *)w_t,
-                       vnorm, d.H, d.G, d.n, d.dm, d.vs[0], d.vs[1], d.vs[2]);
+    const int row_tiles = (d.n + rows_per_wg - 1) / rows_per_wg;
+    const int heads = d.batch * d.H;
+    const long long wgs = 8ll * ((heads + 7) / 8) * row_tiles;
+    hipLaunchKernelGGL((vproj_mfma_kernel<RB>), dim3((unsigned)wgs), dim3(VM_THREADS), 0, s, (const bf16_t *)v,
+                       (const bf16_t *)w_t, vnorm, d.H, d.G, d.n, d.dm, d.vs[0], d.vs[1], d.vs[2], row_tiles, heads);
     return hipGetLastError();
 }
 
