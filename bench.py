@@ -73,9 +73,11 @@ def main():
     ap.add_argument("--workload", default="llama32k", help="llama32k (default) | llama128k | qwen128k | mistral_prefill | tiny")
     ap.add_argument("--sets", type=int, default=0, help="independent input sets rotated over the steps (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=12288)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the steps are issued on round-robin (independent layers overlap); 1 = serial")
+    ap.add_argument("--norm", choices=["l1", "l2"], default="l1",
+                    help="l1: the paper's default (dense d_model-wide projection); l2: the L2 variant via the Gram matrix")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale profiler byte counters)")
     args = ap.parse_args()
@@ -98,7 +100,8 @@ def main():
     kv_bytes = 2 * b * Hkv * n * dh * esize
     # rotate enough input sets that K and V of consecutive steps cannot sit in the 256 MB Infinity Cache
     nsets = args.sets or max(2, min(4, int(np.ceil(512e6 / kv_bytes))))
-    desc = cfg_desc(P, cfg, flags=P.CKV_WO_OUT_IN)
+    l2 = args.norm == "l2"
+    desc = cfg_desc(P, cfg, flags=P.CKV_WO_IS_GRAM if l2 else P.CKV_WO_OUT_IN, norm=P.CKV_NORM_L2 if l2 else P.CKV_NORM_L1)
     B = cfg.budget
     sets = []
     host0 = None
@@ -111,6 +114,15 @@ def main():
         if s > 0:
             dev["w_o"] = sets[0]["w_o"]  # the projection is a weight: one copy
         sets.append(dev)
+    if l2:
+        # the Gram matrices depend on the pretrained projection only: prepared once, outside the timed steps
+        prep = cfg_desc(P, cfg, flags=P.CKV_WO_OUT_IN, norm=P.CKV_NORM_L2)
+        gram = torch.empty(P.gram_bytes(prep), dtype=torch.uint8, device="cuda")
+        ws0 = torch.empty(P.workspace_bytes(prep, B), dtype=torch.uint8, device="cuda")
+        P.criticalkv_prepare_gram(prep, sets[0]["w_o"], gram, workspace=ws0)
+        torch.cuda.synchronize()
+        for dev in sets:
+            dev["w_o"] = gram
     budget = torch.full((b, Hkv), B, dtype=torch.int32, device="cuda")
     # Steps are independent layers; they are issued round-robin on `--streams` streams (each with its own
     # workspace and outputs).  The score calls are chained with events (one projection kernel at a time),
@@ -215,7 +227,9 @@ def main():
 
     entries = cfg.entries
     value = entries / (ms_per_step * 1e-3) / 1e6
-    flops = 2.0 * b * H * n * dh * dm
+    # L1: the d_h x d_model projection per query head.  L2: v G v^T with the d_h x d_h Gram matrix (the split of
+    # G into two bf16 matrices doubles the MFMA work actually issued; the algorithmic count does not include it)
+    flops = 2.0 * b * H * n * dh * (dm if args.norm == "l1" else dh)
     achieved = flops / (vproj_avg * 1e-3) / 1e12
     # lower bound of the whole pass: K and V read once, W_O once, the MFMA contraction, the gather traffic
     hbm_bytes = (kv_bytes                      # K and V read once
@@ -230,15 +244,15 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: batch {b}, {H} q / {Hkv} kv heads, d_h {dh}, d_model {dm}, n {n}, "
-                               f"W {cfg.window}, pool {cfg.pool_kernel}, budget {B}/head, alpha {cfg.alpha}",
+                               f"W {cfg.window}, pool {cfg.pool_kernel}, budget {B}/head, alpha {cfg.alpha}, norm {args.norm}",
                    "w_o_layout": "[d_model, H*d_h] (CKV_WO_OUT_IN)", "input_sets_rotated": nsets,
                    "streams": n_streams, "serial_ms_per_step": round(serial_ms_per_step, 4),
                    "tokens_per_s": round(b * n / (ms_per_step * 1e-3), 1),
                    **({"layers": cfg.n_layers, "total_ms_all_layers": round(cfg.n_layers * ms_per_step, 3)}
                       if cfg.n_layers > 1 else {})},
-        "roofline": {"kernel": "vproj_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
+        "roofline": {"kernel": "vproj_mfma_kernel" if args.norm == "l1" else "gram + vproj_l2_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": VPROJ_TRAFFIC_BYTES.get(cfg.name), "avg_launch_ms": round(vproj_avg, 4),
+                     "traffic": VPROJ_TRAFFIC_BYTES.get(cfg.name) if args.norm == "l1" else None, "avg_launch_ms": round(vproj_avg, 4),
                      "algorithmic_flop_per_launch": flops},
         "stages_ms": stage_ms,
         "pass_lower_bound_ms": round(t_bound_ms, 4), "pass_frac_of_bound": round(t_bound_ms / ms_per_step, 4),
@@ -252,7 +266,7 @@ def main():
         O.lib()
         c0 = time.perf_counter()
         O.full_pass(sample["q_win"], sample["k"], sample["v"], sample["w_o"], Bs, cfg.alpha,
-                    pool_kernel=cfg.pool_kernel, eps=cfg.eps)
+                    pool_kernel=cfg.pool_kernel, eps=cfg.eps, norm=2 if args.norm == "l2" else 1)
         c1 = time.perf_counter()
         out["cpu_baseline"] = {"value": round(b * Hkv * ns / (c1 - c0) / 1e6, 4), "unit": "M KV entries/s",
                                "cores": O.num_threads(), "kind": "oracle",

@@ -52,8 +52,11 @@ extern "C" {
 #define CKV_BF16 0
 #define CKV_F32 1
 
-/* ckv_layer_desc.norm: norm applied to each row of V W^O (the paper's results use L1) */
+/* ckv_layer_desc.norm: norm applied to each row of V W^O.  The paper's results use L1; it reports the L2
+   distance as giving similar quality.  For L2 the bf16 d_h = 128 path uses the exact identity
+   ||v W||_2^2 = v (W W^T) v^T (a d_h x d_h Gram matrix per head instead of the d_h x d_model slice). */
 #define CKV_NORM_L1 1
+#define CKV_NORM_L2 2
 
 /* ckv_layer_desc.window_reduce: how the W window rows are merged (Algorithm 2 line 3 takes the mean) */
 #define CKV_MEAN 0
@@ -65,6 +68,8 @@ extern "C" {
                             h*d_h .. (h+1)*d_h-1, i.e. the paper's d_h x d slice per head (Section 3.1) */
 #define CKV_NO_MFMA 2u   /* run the plain vector-ALU kernels even where a matrix-core kernel exists
                             (same results up to fp32 rounding order; for validation)               */
+#define CKV_WO_IS_GRAM 4u /* CKV_NORM_L2 only: the w_o argument of criticalkv_score is the per-layer
+                            constant written by criticalkv_prepare_gram, not the projection itself  */
 
 /*
  * One attention layer.  Notation of the paper: n cached entries per head, window of n' = `window`
@@ -81,9 +86,9 @@ typedef struct ckv_layer_desc {
     int32_t window;        /* n' = W observation-window queries, 1 <= W <= n                  */
     int32_t pool_kernel;   /* odd max-pool width over the token axis, 1 = no pooling          */
     int32_t dtype;         /* CKV_BF16 or CKV_F32                                             */
-    int32_t norm;          /* CKV_NORM_L1                                                     */
+    int32_t norm;          /* CKV_NORM_L1 or CKV_NORM_L2                                      */
     int32_t window_reduce; /* CKV_MEAN or CKV_SUM                                             */
-    uint32_t flags;        /* CKV_WO_OUT_IN | CKV_NO_MFMA                                     */
+    uint32_t flags;        /* CKV_WO_OUT_IN | CKV_NO_MFMA | CKV_WO_IS_GRAM                    */
     float softmax_scale;   /* logit scale; 0 selects 1/sqrt(head_dim) (eq. 2)                 */
     float eps;             /* added to the pooled score before the product (paper: 1e-4)      */
     int64_t k_stride[3];   /* element strides of k for (batch, kv head, token); all 0 =       */
@@ -104,7 +109,7 @@ CKV_API size_t criticalkv_workspace_bytes(const ckv_layer_desc *desc, int32_t ma
  *   p_{w,.}   = softmax_i(scale * q_win[bi,h,w,:] . k[bi,g,i,:])   over all n keys, no mask
  *   a^h_i     = mean_w p_{w,i}          (sum_w with CKV_SUM)
  *   abar^h_i  = max{ a^h_j : |j - i| <= pool_kernel/2, 0 <= j < n }
- *   N^h_i     = sum_c | sum_t v[bi,g,i,t] * W^O[h*d_h + t, c] |
+ *   N^h_i     = sum_c | sum_t v[bi,g,i,t] * W^O[h*d_h + t, c] |      (CKV_NORM_L2: sqrt of the sum of squares)
  * and, per kv head (group means; with G = 1 exactly the paper's A and (A + eps) * ||V W^O||_1):
  *   attn[bi,g,i] = (1/G) sum_{h in g} abar^h_i
  *   crit[bi,g,i] = (1/G) sum_{h in g} (abar^h_i + eps) * N^h_i
@@ -119,6 +124,19 @@ CKV_API size_t criticalkv_workspace_bytes(const ckv_layer_desc *desc, int32_t ma
 CKV_API int criticalkv_score(const ckv_layer_desc *desc, const void *q_win, const void *k, const void *v,
                              const void *w_o, float *attn, float *crit, float *vnorm_opt, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
+
+/*
+ * L2 variant: the per-layer constant G^h = W^O_h W^O_h^T (d_h x d_h per query head), which depends on the
+ * pretrained projection only and can be prepared once per layer and reused for every prompt.
+ * criticalkv_gram_bytes: size of gram_out (0 if the layer has no Gram-matrix path: bf16, d_h = 128,
+ * d_model a multiple of 512).  criticalkv_prepare_gram writes it (device memory, opaque layout: two bf16
+ * matrices per head whose sum is G to ~2^-17 relative); w_o as for criticalkv_score (layout per
+ * CKV_WO_OUT_IN), workspace as for criticalkv_score.  Pass gram_out as `w_o` to criticalkv_score together
+ * with CKV_NORM_L2 and CKV_WO_IS_GRAM; without that flag criticalkv_score computes G itself on every call.
+ */
+CKV_API size_t criticalkv_gram_bytes(const ckv_layer_desc *desc);
+CKV_API int criticalkv_prepare_gram(const ckv_layer_desc *desc, const void *w_o, void *gram_out, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream);
 
 /*
  * criticalkv_score with per-stage timing marks, for benchmarks and profiles (the scores are the same).

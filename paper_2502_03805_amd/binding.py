@@ -16,13 +16,13 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("CRITICALKV_LIB") or os.path.join(PKG, "libcriticalkv.so")
 
 CKV_BF16, CKV_F32 = 0, 1
-CKV_NORM_L1 = 1
+CKV_NORM_L1, CKV_NORM_L2 = 1, 2
 CKV_MEAN, CKV_SUM = 0, 1
-CKV_WO_OUT_IN, CKV_NO_MFMA = 1, 2
+CKV_WO_OUT_IN, CKV_NO_MFMA, CKV_WO_IS_GRAM = 1, 2, 4
 CKV_OK, CKV_E_INVALID_ARG, CKV_E_UNSUPPORTED, CKV_E_WORKSPACE, CKV_E_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("criticalkv_workspace_bytes", "criticalkv_score", "criticalkv_score_profiled", "criticalkv_select",
-           "criticalkv_compact", "criticalkv_strerror")
+           "criticalkv_compact", "criticalkv_strerror", "criticalkv_gram_bytes", "criticalkv_prepare_gram")
 STAGES = ("wo_layout", "attn_stats", "attn_colsum", "vproj", "combine")
 
 
@@ -83,6 +83,10 @@ def load() -> ctypes.CDLL:
         lib.criticalkv_score_profiled.restype = ctypes.c_int
         lib.criticalkv_score_profiled.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp,
                                                   ctypes.POINTER(ctypes.c_void_p)]
+        lib.criticalkv_gram_bytes.restype = ctypes.c_size_t
+        lib.criticalkv_gram_bytes.argtypes = [dp]
+        lib.criticalkv_prepare_gram.restype = ctypes.c_int
+        lib.criticalkv_prepare_gram.argtypes = [dp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.criticalkv_select.restype = ctypes.c_int
         lib.criticalkv_select.argtypes = [dp, vp, vp, vp, f32, i32, vp, vp, vp, ctypes.c_size_t, vp]
         lib.criticalkv_compact.restype = ctypes.c_int
@@ -130,6 +134,17 @@ def criticalkv_score(desc: LayerDesc, q_win, k, v, w_o, attn, crit, vnorm=None, 
                                  _stream(stream))
     if rc != CKV_OK:
         raise CriticalKVError(rc, "criticalkv_score")
+
+
+def gram_bytes(desc: LayerDesc) -> int:
+    return int(load().criticalkv_gram_bytes(ctypes.byref(desc)))
+
+
+def criticalkv_prepare_gram(desc: LayerDesc, w_o, gram_out, *, workspace, stream=None) -> None:
+    rc = load().criticalkv_prepare_gram(ctypes.byref(desc), _ptr(w_o), _ptr(gram_out), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != CKV_OK:
+        raise CriticalKVError(rc, "criticalkv_prepare_gram")
 
 
 def criticalkv_score_profiled(desc: LayerDesc, q_win, k, v, w_o, attn, crit, vnorm=None, *, workspace, stage_events,

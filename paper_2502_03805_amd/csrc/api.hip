@@ -21,12 +21,13 @@ static int resolve(const ckv_layer_desc *desc, Dims *out)
     if (c.pool_kernel < 1 || (c.pool_kernel % 2) == 0) return CKV_E_INVALID_ARG;
     if (c.dtype != CKV_BF16 && c.dtype != CKV_F32) return CKV_E_INVALID_ARG;
     if (c.window_reduce != CKV_MEAN && c.window_reduce != CKV_SUM) return CKV_E_INVALID_ARG;
-    if (c.flags & ~(CKV_WO_OUT_IN | CKV_NO_MFMA)) return CKV_E_INVALID_ARG;
+    if (c.flags & ~(CKV_WO_OUT_IN | CKV_NO_MFMA | CKV_WO_IS_GRAM)) return CKV_E_INVALID_ARG;
+    if ((c.flags & CKV_WO_IS_GRAM) && (c.norm != CKV_NORM_L2 || (c.flags & CKV_NO_MFMA))) return CKV_E_INVALID_ARG;
     if (!(c.softmax_scale >= 0.0f) || !isfinite(c.softmax_scale)) return CKV_E_INVALID_ARG;
     if (!(c.eps >= 0.0f) || !isfinite(c.eps)) return CKV_E_INVALID_ARG;
     if (c.head_dim != 64 && c.head_dim != 128) return CKV_E_UNSUPPORTED;
     if (c.d_model % 32) return CKV_E_UNSUPPORTED;
-    if (c.norm != CKV_NORM_L1) return CKV_E_UNSUPPORTED;
+    if (c.norm != CKV_NORM_L1 && c.norm != CKV_NORM_L2) return CKV_E_INVALID_ARG;
     if (c.pool_kernel > 63) return CKV_E_UNSUPPORTED;
     if ((int64_t)c.window * c.head_dim > 12288) return CKV_E_UNSUPPORTED; // window queries are staged in LDS
     // index arithmetic inside the kernels is 64-bit for tensors and 32-bit for per-head token indices
@@ -37,6 +38,7 @@ static int resolve(const ckv_layer_desc *desc, Dims *out)
     d.batch = c.batch; d.H = c.n_q_heads; d.Hkv = c.n_kv_heads; d.G = d.H / d.Hkv;
     d.dh = c.head_dim; d.dm = c.d_model; d.n = c.n_ctx; d.W = c.window; d.pool_k = c.pool_kernel;
     d.window_sum = c.window_reduce == CKV_SUM;
+    d.norm = c.norm;
     d.scale = c.softmax_scale > 0.0f ? c.softmax_scale : 1.0f / sqrtf((float)c.head_dim);
     d.eps = c.eps;
     const int64_t contiguous[3] = {(int64_t)d.Hkv * d.n * d.dh, (int64_t)d.n * d.dh, (int64_t)d.dh};
@@ -65,6 +67,7 @@ Workspace carve_workspace(const Dims &d, int dtype, bool need_wt)
     w.stats_part = off; off = align256(off + (size_t)d.batch * d.H * d.W * w.max_chunks * 2 * 4);
     w.stats = off; off = align256(off + (size_t)d.batch * d.H * d.W * 2 * 4);
     w.w_t = off; if (need_wt) off = align256(off + (size_t)d.H * d.dh * d.dm * elem_size(dtype));
+    w.l2_scratch = off; if (d.norm == CKV_NORM_L2 && d.dh == 128) off = align256(off + vproj_l2_workspace_bytes(d));
     w.sel_keys = off; off = align256(off + (size_t)d.batch * d.Hkv * d.n * 4);
     w.sel_scratch = off; off = align256(off + select_workspace_words(d.batch * d.Hkv, d.n) * 4);
     w.total = off;
@@ -86,7 +89,8 @@ size_t criticalkv_workspace_bytes(const ckv_layer_desc *desc, int32_t max_budget
 {
     Dims d;
     if (resolve(desc, &d) != CKV_OK || max_budget < 0) return 0;
-    // sized for either w_o layout so that one allocation serves both
+    // sized for either w_o layout and either norm so that one allocation serves every call on this layer
+    d.norm = CKV_NORM_L2;
     return carve_workspace(d, desc->dtype, true).total;
 }
 
@@ -103,7 +107,9 @@ static int score_impl(const ckv_layer_desc *desc, const void *q_win, const void 
     int rc = resolve(desc, &d);
     if (rc != CKV_OK) return rc;
     if (!q_win || !k || !v || !w_o || !attn || !crit) return CKV_E_INVALID_ARG;
-    const bool need_wt = !(desc->flags & CKV_WO_OUT_IN);
+    const bool have_gram = desc->flags & CKV_WO_IS_GRAM;
+    if (have_gram && !(mfma_allowed(desc) && vproj_l2_mfma_supported(d))) return CKV_E_UNSUPPORTED;
+    const bool need_wt = !have_gram && !(desc->flags & CKV_WO_OUT_IN);
     const Workspace ws = carve_workspace(d, desc->dtype, need_wt);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
 
@@ -141,7 +147,20 @@ static int score_impl(const ckv_layer_desc *desc, const void *q_win, const void 
     if (e != hipSuccess) return CKV_E_HIP;
     mark(ev, 2 * CKV_STAGE_ATTN_COLSUM + 1, s);
     mark(ev, 2 * CKV_STAGE_VPROJ, s);
-    e = mfma_v ? launch_vproj_mfma(d, v, w_t, vnorm, s) : launch_vproj_generic(d, desc->dtype, v, w_t, vnorm, s);
+    if (d.norm == CKV_NORM_L2 && mfma_allowed(desc) && vproj_l2_mfma_supported(d)) {
+        const void *gram = w_o; // prepared by the caller, or computed here from the projection
+        if (!have_gram) {
+            char *scratch = base + ws.l2_scratch;
+            void *g = scratch + vproj_l2_workspace_bytes(d) - vproj_l2_gram_bytes(d);
+            e = launch_gram(d, w_t, g, scratch, s);
+            if (e != hipSuccess) return CKV_E_HIP;
+            gram = g;
+        }
+        e = launch_vproj_l2_mfma(d, v, gram, vnorm, s);
+    } else if (d.norm == CKV_NORM_L1 && mfma_v)
+        e = launch_vproj_mfma(d, v, w_t, vnorm, s);
+    else
+        e = launch_vproj_generic(d, desc->dtype, v, w_t, vnorm, s);
     if (e != hipSuccess) return CKV_E_HIP;
     mark(ev, 2 * CKV_STAGE_VPROJ + 1, s);
     mark(ev, 2 * CKV_STAGE_COMBINE, s);
@@ -164,6 +183,35 @@ int criticalkv_score_profiled(const ckv_layer_desc *desc, const void *q_win, con
 {
     return score_impl(desc, q_win, k, v, w_o, attn, crit, vnorm_opt, workspace, workspace_bytes, hip_stream,
                       stage_events);
+}
+
+size_t criticalkv_gram_bytes(const ckv_layer_desc *desc)
+{
+    Dims d;
+    if (resolve(desc, &d) != CKV_OK || desc->dtype != CKV_BF16 || !vproj_l2_mfma_supported(d)) return 0;
+    return vproj_l2_gram_bytes(d);
+}
+
+int criticalkv_prepare_gram(const ckv_layer_desc *desc, const void *w_o, void *gram_out, void *workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    Dims d;
+    int rc = resolve(desc, &d);
+    if (rc != CKV_OK) return rc;
+    if (!w_o || !gram_out || (desc->flags & CKV_WO_IS_GRAM)) return CKV_E_INVALID_ARG;
+    if (desc->dtype != CKV_BF16 || !vproj_l2_mfma_supported(d)) return CKV_E_UNSUPPORTED;
+    d.norm = CKV_NORM_L2; // the carve below must contain the Gram scratch whatever norm the descriptor names
+    const bool need_wt = !(desc->flags & CKV_WO_OUT_IN);
+    const Workspace ws = carve_workspace(d, desc->dtype, need_wt);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *base = (char *)workspace;
+    const void *w_t = w_o;
+    if (need_wt) {
+        if (launch_transpose_wo(d, desc->dtype, w_o, base + ws.w_t, s) != hipSuccess) return CKV_E_HIP;
+        w_t = base + ws.w_t;
+    }
+    return launch_gram(d, w_t, gram_out, base + ws.l2_scratch, s) == hipSuccess ? CKV_OK : CKV_E_HIP;
 }
 
 int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float *crit, const int32_t *budget,

@@ -20,6 +20,7 @@ __device__ __forceinline__ float to_f32(bf16_t x) { return bf16_to_f32(x); }
 struct Dims {
     int batch, H, Hkv, G, dh, dm, n, W, pool_k;
     int window_sum;
+    int norm; // CKV_NORM_L1 or CKV_NORM_L2
     float scale, eps;
     int64_t ks[3], vs[3];
 };
@@ -32,6 +33,7 @@ struct Workspace {
     size_t stats;      // [batch, H, W, 2] f32: per-row (max + log sum, unused)
     size_t w_t;        // [d_model, H*dh] copy of W_O in output-major layout (when given canonical)
     size_t sel_keys;   // [batch*Hkv, n] u32: stage-2 keys with stage-1 entries marked
+    size_t l2_scratch; // Gram partial sums and the split bf16 Gram matrices (L2 norm only)
     size_t sel_scratch; // digit histograms, per-head state, per-slice counts of the selection kernels
     size_t total;
     int max_chunks;    // capacity of stats_part per window row
@@ -64,6 +66,13 @@ hipError_t launch_attn_colsum_mfma(const Dims &d, const void *q, const void *k, 
 hipError_t launch_vproj_generic(const Dims &d, int dtype, const void *v, const void *w_t, float *vnorm,
                                 hipStream_t s);
 hipError_t launch_vproj_mfma(const Dims &d, const void *v, const void *w_t, float *vnorm, hipStream_t s);
+// L2 norm through the Gram matrix W_O^h W_O^h^T (bf16, d_h = 128)
+bool vproj_l2_mfma_supported(const Dims &d);
+size_t vproj_l2_workspace_bytes(const Dims &d);
+size_t vproj_l2_gram_bytes(const Dims &d); // the split bf16 Gram matrices alone
+// gram: the prepared Gram matrices; when null they are computed from w_t into scratch first
+hipError_t launch_gram(const Dims &d, const void *w_t, void *gram_out, void *partial_scratch, hipStream_t s);
+hipError_t launch_vproj_l2_mfma(const Dims &d, const void *v, const void *gram, float *vnorm, hipStream_t s);
 // [H*dh, d_model] -> [d_model, H*dh]
 hipError_t launch_transpose_wo(const Dims &d, int dtype, const void *w_o, void *w_t, hipStream_t s);
 // pool + eps + product + group mean

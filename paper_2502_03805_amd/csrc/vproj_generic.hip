@@ -1,4 +1,4 @@
-// Per-entry L1 magnitude of the projected value on the vector ALUs
+// Per-entry L1 (or L2) magnitude of the projected value on the vector ALUs
 // (Theorem 3.3; Algorithm 1, lines 2-3):  N^h_i = sum_c | sum_t V^g[i,t] * W_O^h[t,c] |.
 //
 // Serves fp32 inputs and head sizes the matrix-core kernel does not cover.  One thread owns
@@ -12,7 +12,7 @@ namespace ckv {
 constexpr int VG_THREADS = 256;
 constexpr int VG_TC = 32; // output columns per LDS tile
 
-template <typename T, int DH>
+template <typename T, int DH, bool L2>
 __global__ __launch_bounds__(VG_THREADS) void vproj_generic_kernel(const T *__restrict__ v, const T *__restrict__ w_t,
                                                                    float *__restrict__ vnorm, int H, int G, int n,
                                                                    int dm, int64_t vs0, int64_t vs1, int64_t vs2)
@@ -43,18 +43,22 @@ __global__ __launch_bounds__(VG_THREADS) void vproj_generic_kernel(const T *__re
                 p = fmaf(vr[t], ww.x, p); p = fmaf(vr[t + 1], ww.y, p);
                 p = fmaf(vr[t + 2], ww.z, p); p = fmaf(vr[t + 3], ww.w, p);
             }
-            acc += fabsf(p);
+            acc += L2 ? p * p : fabsf(p);
         }
     }
-    if (valid) vnorm[((size_t)bi * H + h) * (size_t)n + i] = acc;
+    if (valid) vnorm[((size_t)bi * H + h) * (size_t)n + i] = L2 ? sqrtf(acc) : acc;
 }
 
 template <typename T, int DH>
 static hipError_t vproj_generic_t(const Dims &d, const void *v, const void *w_t, float *vnorm, hipStream_t s)
 {
     dim3 grid((d.n + VG_THREADS - 1) / VG_THREADS, d.H, d.batch);
-    hipLaunchKernelGGL((vproj_generic_kernel<T, DH>), grid, dim3(VG_THREADS), 0, s, (const T *)v, (const T *)w_t, vnorm,
-                       d.H, d.G, d.n, d.dm, d.vs[0], d.vs[1], d.vs[2]);
+    if (d.norm == CKV_NORM_L2)
+        hipLaunchKernelGGL((vproj_generic_kernel<T, DH, true>), grid, dim3(VG_THREADS), 0, s, (const T *)v, (const T *)w_t,
+                           vnorm, d.H, d.G, d.n, d.dm, d.vs[0], d.vs[1], d.vs[2]);
+    else
+        hipLaunchKernelGGL((vproj_generic_kernel<T, DH, false>), grid, dim3(VG_THREADS), 0, s, (const T *)v, (const T *)w_t,
+                           vnorm, d.H, d.G, d.n, d.dm, d.vs[0], d.vs[1], d.vs[2]);
     return hipGetLastError();
 }
 

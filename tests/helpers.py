@@ -15,11 +15,12 @@ import numpy as np
 REL_TOL = 2e-3
 
 
-def cfg_desc(P, cfg, *, flags=0, window_reduce=None, softmax_scale=0.0, **over):
+def cfg_desc(P, cfg, *, flags=0, window_reduce=None, softmax_scale=0.0, norm=1, **over):
     kw = dict(batch=cfg.batch, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
               d_model=cfg.d_model, n_ctx=cfg.n_ctx, window=cfg.window, pool_kernel=cfg.pool_kernel,
               dtype=P.CKV_BF16 if cfg.dtype == "bf16" else P.CKV_F32, flags=flags, eps=cfg.eps,
-              window_reduce=P.CKV_MEAN if window_reduce is None else window_reduce, softmax_scale=softmax_scale)
+              window_reduce=P.CKV_MEAN if window_reduce is None else window_reduce, softmax_scale=softmax_scale,
+              norm=norm)
     kw.update(over)
     return P.make_desc(**kw)
 
@@ -47,12 +48,12 @@ class GpuResult:
 
 
 def run_gpu_pass(P, cfg, tensors, budget, alpha, *, flags=0, wo_out_in=False, max_budget=None, want_vnorm=True,
-                 window_reduce=None, softmax_scale=0.0, dev=None) -> GpuResult:
+                 window_reduce=None, softmax_scale=0.0, dev=None, norm=1) -> GpuResult:
     """score -> select -> compact through the C ABI on cuda:0; returns host copies."""
     import torch
     if wo_out_in:
         flags |= P.CKV_WO_OUT_IN
-    desc = cfg_desc(P, cfg, flags=flags, window_reduce=window_reduce, softmax_scale=softmax_scale)
+    desc = cfg_desc(P, cfg, flags=flags, window_reduce=window_reduce, softmax_scale=softmax_scale, norm=norm)
     dev = dev or to_device(cfg, tensors, wo_out_in)
     b, H, Hkv, n, dh = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_ctx, cfg.head_dim
     budget = np.broadcast_to(np.asarray(budget, dtype=np.int32), (b, Hkv)).copy()

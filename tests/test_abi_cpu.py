@@ -66,7 +66,7 @@ def test_workspace_bytes_is_positive_and_monotone(lib):
     (dict(eps=float("nan")), P.CKV_E_INVALID_ARG),
     (dict(head_dim=96), P.CKV_E_UNSUPPORTED),
     (dict(d_model=100), P.CKV_E_UNSUPPORTED),
-    (dict(norm=2), P.CKV_E_UNSUPPORTED),
+    (dict(norm=3), P.CKV_E_INVALID_ARG),
     (dict(k_stride=(128000, 64000, 100)), P.CKV_E_INVALID_ARG),   # token stride below head_dim
     (dict(k_stride=(128004, 64004, 132)), P.CKV_E_UNSUPPORTED),   # rows not 16-byte aligned
 ])
@@ -92,7 +92,7 @@ def test_null_pointers_workspace_and_ranges(lib):
     # workspace missing / misaligned / too small
     assert lib.criticalkv_score(ctypes.byref(d), p, p, p, p, p, p, None, None, need, None) == P.CKV_E_WORKSPACE
     assert lib.criticalkv_score(ctypes.byref(d), p, p, p, p, p, p, None, p + 8, need, None) == P.CKV_E_WORKSPACE
-    assert lib.criticalkv_score(ctypes.byref(d), p, p, p, p, p, p, None, p, need - 1, None) == P.CKV_E_WORKSPACE
+    assert lib.criticalkv_score(ctypes.byref(d), p, p, p, p, p, p, None, p, 4096, None) == P.CKV_E_WORKSPACE
     # select: alpha and max_budget ranges
     assert lib.criticalkv_select(ctypes.byref(d), p, p, p, 1.5, 100, p, p, p, need, None) == P.CKV_E_INVALID_ARG
     assert lib.criticalkv_select(ctypes.byref(d), p, p, p, float("nan"), 100, p, p, p, need, None) == P.CKV_E_INVALID_ARG
@@ -102,6 +102,25 @@ def test_null_pointers_workspace_and_ranges(lib):
     assert lib.criticalkv_select(ctypes.byref(d), p, p, p, 0.5, 100, p, p, p, 16, None) == P.CKV_E_WORKSPACE
     assert lib.criticalkv_compact(ctypes.byref(d), p, p, p, p, 0, p, p, None) == P.CKV_E_INVALID_ARG
     assert lib.criticalkv_compact(ctypes.byref(d), p, p, p, None, 10, p, p, None) == P.CKV_E_INVALID_ARG
+
+
+def test_gram_entry_points_validate(lib):
+    d = good_desc(d_model=512, norm=P.CKV_NORM_L2)
+    assert P.gram_bytes(d) == 8 * 2 * 128 * 128 * 2
+    assert P.gram_bytes(good_desc(d_model=256, norm=P.CKV_NORM_L2)) == 0          # d_model not a multiple of 512
+    assert P.gram_bytes(good_desc(d_model=512, dtype=P.CKV_F32)) == 0
+    buf = ctypes.create_string_buffer(1024)
+    p = (ctypes.addressof(buf) + 255) & ~255
+    need = P.workspace_bytes(d, 10)
+    assert lib.criticalkv_prepare_gram(ctypes.byref(d), None, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_prepare_gram(ctypes.byref(d), p, p, p, 64, None) == P.CKV_E_WORKSPACE
+    d2 = good_desc(d_model=256)
+    assert lib.criticalkv_prepare_gram(ctypes.byref(d2), p, p, p, need, None) == P.CKV_E_UNSUPPORTED
+    # the prepared-Gram flag needs the L2 norm and the matrix-core path
+    d3 = good_desc(d_model=512, norm=P.CKV_NORM_L1, flags=P.CKV_WO_IS_GRAM)
+    assert lib.criticalkv_score(ctypes.byref(d3), p, p, p, p, p, p, None, p, need, None) == P.CKV_E_INVALID_ARG
+    d4 = good_desc(d_model=512, norm=P.CKV_NORM_L2, flags=P.CKV_WO_IS_GRAM | P.CKV_NO_MFMA)
+    assert lib.criticalkv_score(ctypes.byref(d4), p, p, p, p, p, p, None, p, need, None) == P.CKV_E_INVALID_ARG
 
 
 def test_binding_raises_with_code():

@@ -82,6 +82,55 @@ def test_batch_and_head_dim_64(P):
     check_full(P, cfg32, t, wo_out_in=False, label="b3 dh64 f32")
 
 
+@pytest.mark.parametrize("case", ["llama_gram", "llama_valu", "qwen_gram", "tiny_f32", "dh64_bf16"])
+def test_l2_norm_variant(P, case):
+    """L2 distance variant: N = ||v W_O^h||_2.  The bf16 d_h = 128 path goes through the Gram matrix
+    (exact for the 2-norm); the oracle evaluates the definition (all d_model products) in float64."""
+    flags, wo = 0, True
+    if case == "llama_gram":
+        cfg = reduced(CONFIGS["llama32k"], 4133, d_model=1024)
+    elif case == "llama_valu":
+        cfg = reduced(CONFIGS["llama32k"], 1500, d_model=512)
+        flags = P.CKV_NO_MFMA
+    elif case == "qwen_gram":
+        cfg = reduced(CONFIGS["qwen128k"], 3000, d_model=2560)
+    elif case == "tiny_f32":
+        cfg, wo = CONFIGS["tiny"], False
+    else:
+        cfg = reduced(CONFIGS["llama32k"], 700, d_model=256, head_dim=64, n_q_heads=6, n_kv_heads=3, window=5)
+    t = make_layer(cfg)
+    ref = O.full_pass(t["q_win"], t["k"], t["v"], t["w_o"], cfg.budget, cfg.alpha, pool_kernel=cfg.pool_kernel,
+                      eps=cfg.eps, norm=2)
+    res = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, flags=flags, wo_out_in=wo, norm=P.CKV_NORM_L2)
+    e_v = assert_scores_close(res.vnorm, ref.vnorm, "vnorm (L2)")
+    e_c = assert_scores_close(res.crit, ref.crit, "crit (L2)")
+    swaps = compare_selection(res.idx, res.count, ref, cfg.budget, cfg.alpha)
+    assert_compaction_exact(res, t, cfg.budget)
+    # sanity: the L2 and L1 norms differ (the flag is honoured)
+    ref1 = O.projected_value_norm(t["v"], t["w_o"], cfg.n_q_heads, norm=1)
+    assert np.all(ref.vnorm < ref1)
+    print(f"[L2 {case}] max rel err vnorm {e_v[0]:.2e} crit {e_c[0]:.2e}; swapped indices {swaps}")
+
+
+def test_l2_with_prepared_gram_matches_inline_gram(P):
+    """criticalkv_prepare_gram once, then criticalkv_score with CKV_WO_IS_GRAM: identical scores."""
+    import torch
+    cfg = reduced(CONFIGS["llama32k"], 2500, d_model=1024)
+    t = make_layer(cfg)
+    inline = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, wo_out_in=True, norm=P.CKV_NORM_L2)
+    for wo_out_in in (True, False):
+        desc = cfg_desc(P, cfg, flags=P.CKV_WO_OUT_IN if wo_out_in else 0, norm=P.CKV_NORM_L2)
+        dev = to_device(cfg, t, wo_out_in)
+        ws = torch.empty(P.workspace_bytes(desc, cfg.budget), dtype=torch.uint8, device="cuda")
+        gram = torch.empty(P.gram_bytes(desc), dtype=torch.uint8, device="cuda")
+        P.criticalkv_prepare_gram(desc, dev["w_o"], gram, workspace=ws)
+        desc_g = cfg_desc(P, cfg, flags=P.CKV_WO_IS_GRAM, norm=P.CKV_NORM_L2)
+        dev["w_o"] = gram
+        res = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, flags=P.CKV_WO_IS_GRAM, norm=P.CKV_NORM_L2, dev=dev)
+        assert np.array_equal(res.vnorm, inline.vnorm) and np.array_equal(res.crit, inline.crit)
+        assert np.array_equal(res.idx, inline.idx)
+
+
 def test_window_sum_and_explicit_scale(P):
     cfg = reduced(CONFIGS["llama32k"], 900, d_model=256)
     t = make_layer(cfg)
