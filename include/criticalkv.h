@@ -68,6 +68,11 @@ extern "C" {
                             h*d_h .. (h+1)*d_h-1, i.e. the paper's d_h x d slice per head (Section 3.1) */
 #define CKV_NO_MFMA 2u   /* run the plain vector-ALU kernels even where a matrix-core kernel exists
                             (same results up to fp32 rounding order; for validation)               */
+#define CKV_CAUSAL_TAIL 8u /* the window queries are the last W tokens of the prompt and attend causally:
+                            window row w (position n-W+w) sees keys 0 .. n-W+w only (chunked prefill);
+                            without it every window row sees all n keys (the algorithm as printed)    */
+#define CKV_PROTECT_WINDOW 16u /* the last W entries (the window's own tokens) are always kept while the
+                            budget allows: their attn and crit are set to FLT_MAX (ties: index order)   */
 #define CKV_WO_IS_GRAM 4u /* CKV_NORM_L2 only: the w_o argument of criticalkv_score is the per-layer
                             constant written by criticalkv_prepare_gram, not the projection itself  */
 
@@ -88,7 +93,7 @@ typedef struct ckv_layer_desc {
     int32_t dtype;         /* CKV_BF16 or CKV_F32                                             */
     int32_t norm;          /* CKV_NORM_L1 or CKV_NORM_L2                                      */
     int32_t window_reduce; /* CKV_MEAN or CKV_SUM                                             */
-    uint32_t flags;        /* CKV_WO_OUT_IN | CKV_NO_MFMA | CKV_WO_IS_GRAM                    */
+    uint32_t flags;        /* CKV_WO_OUT_IN | CKV_NO_MFMA | CKV_WO_IS_GRAM | CKV_CAUSAL_TAIL | ... */
     float softmax_scale;   /* logit scale; 0 selects 1/sqrt(head_dim) (eq. 2)                 */
     float eps;             /* added to the pooled score before the product (paper: 1e-4)      */
     int64_t k_stride[3];   /* element strides of k for (batch, kv head, token); all 0 =       */

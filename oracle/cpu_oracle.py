@@ -63,7 +63,8 @@ def num_threads() -> int:
     return int(lib().ckvo_num_threads())
 
 
-def window_attention(q_win, k, scale: Optional[float] = None, window_sum: bool = False) -> np.ndarray:
+def window_attention(q_win, k, scale: Optional[float] = None, window_sum: bool = False,
+                     causal_tail: bool = False) -> np.ndarray:
     """a[b,H,n]: softmax over all n keys per window row, mean (or sum) over the window."""
     q_win, qp = _f32(q_win)
     k, kp = _f32(k)
@@ -73,7 +74,7 @@ def window_attention(q_win, k, scale: Optional[float] = None, window_sum: bool =
     if scale is None:
         scale = 1.0 / np.sqrt(dh)
     a = np.empty((b, H, n), dtype=np.float64)
-    rc = lib().ckvo_window_attention(b, H, Hkv, dh, n, W, ctypes.c_double(scale), int(window_sum), qp, kp,
+    rc = lib().ckvo_window_attention(b, H, Hkv, dh, n, W, ctypes.c_double(scale), int(window_sum), int(causal_tail), qp, kp,
                                      a.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
     _check(rc, "window_attention")
     return a
@@ -103,13 +104,13 @@ def projected_value_norm(v, w_o, n_q_heads: int, norm: int = 1) -> np.ndarray:
     return N
 
 
-def group_keys(abar, N, n_kv_heads: int, eps: float = 1e-4):
+def group_keys(abar, N, n_kv_heads: int, eps: float = 1e-4, protect_last: int = 0):
     abar, ap = _f64(abar)
     N, Np = _f64(N)
     b, H, n = abar.shape
     attn = np.empty((b, n_kv_heads, n), dtype=np.float64)
     crit = np.empty((b, n_kv_heads, n), dtype=np.float64)
-    rc = lib().ckvo_group_keys(b, H, n_kv_heads, n, ctypes.c_double(eps), ap, Np,
+    rc = lib().ckvo_group_keys(b, H, n_kv_heads, n, ctypes.c_double(eps), int(protect_last), ap, Np,
                                attn.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
                                crit.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
     _check(rc, "group_keys")
@@ -182,20 +183,23 @@ class OracleResult:
 
 
 def score(q_win, k, v, w_o, *, pool_kernel: int, eps: float = 1e-4, scale: Optional[float] = None,
-          window_sum: bool = False, norm: int = 1) -> OracleResult:
+          window_sum: bool = False, norm: int = 1, causal_tail: bool = False,
+          protect_window: bool = False) -> OracleResult:
     H = q_win.shape[1]
     Hkv = k.shape[1]
-    a = window_attention(q_win, k, scale, window_sum)
+    a = window_attention(q_win, k, scale, window_sum, causal_tail)
     abar = maxpool1d(a, pool_kernel)
     N = projected_value_norm(v, w_o, H, norm)
-    attn, crit = group_keys(abar, N, Hkv, eps)
+    attn, crit = group_keys(abar, N, Hkv, eps, q_win.shape[2] if protect_window else 0)
     return OracleResult(a, abar, N, attn, crit)
 
 
 def full_pass(q_win, k, v, w_o, budget, alpha: float, *, pool_kernel: int, eps: float = 1e-4,
               scale: Optional[float] = None, window_sum: bool = False, norm: int = 1,
-              max_budget: Optional[int] = None) -> OracleResult:
-    r = score(q_win, k, v, w_o, pool_kernel=pool_kernel, eps=eps, scale=scale, window_sum=window_sum, norm=norm)
+              max_budget: Optional[int] = None, causal_tail: bool = False,
+              protect_window: bool = False) -> OracleResult:
+    r = score(q_win, k, v, w_o, pool_kernel=pool_kernel, eps=eps, scale=scale, window_sum=window_sum, norm=norm,
+              causal_tail=causal_tail, protect_window=protect_window)
     r.idx, r.count, r.tau = select(r.attn, r.crit, budget, alpha, max_budget)
     r.k_out = compact(k, r.idx, r.count)
     r.v_out = compact(v, r.idx, r.count)

@@ -54,13 +54,17 @@ int ckvo_num_threads(void)
  *     p_{w,.} = softmax_i(s_{w,.})                               (all n keys, no mask)
  *     a[bi,h,i] = (1/W) sum_w p_{w,i}      or   sum_w p_{w,i}  when window_sum != 0
  *
+ * causal_tail != 0 (chunked-prefill reading): the window queries are the last W tokens of the prompt,
+ * window row w sits at position n - W + w and attends to keys i <= n - W + w only (the usual causal mask,
+ * which only bites inside the last W keys); masked weights are exactly 0.
+ *
  * q_win [b,H,W,d_h], k [b,Hkv,n,d_h], a [b,H,n]; row-major, contiguous.
  */
 int ckvo_window_attention(int b, int H, int Hkv, int d_h, int n, int W,
-                          double scale, int window_sum,
+                          double scale, int window_sum, int causal_tail,
                           const float *q_win, const float *k, double *a)
 {
-    if (b < 1 || H < 1 || Hkv < 1 || H % Hkv || d_h < 1 || n < 1 || W < 1) return CKVO_BAD_ARG;
+    if (b < 1 || H < 1 || Hkv < 1 || H % Hkv || d_h < 1 || n < 1 || W < 1 || W > n) return CKVO_BAD_ARG;
     const int G = H / Hkv;
     int err = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic)
@@ -78,16 +82,17 @@ int ckvo_window_attention(int b, int H, int Hkv, int d_h, int n, int W,
             for (int i = 0; i < n; ++i) out[i] = 0.0;
             for (int w = 0; w < W; ++w) {
                 const float *qq = q_win + (((size_t)bi * H + h) * W + w) * (size_t)d_h;
+                const int visible = causal_tail ? n - W + w + 1 : n; /* keys 0 .. visible-1 */
                 double smax = -INFINITY;
-                for (int i = 0; i < n; ++i) {
+                for (int i = 0; i < visible; ++i) {
                     double dot = 0.0;
                     for (int t = 0; t < d_h; ++t) dot += (double)qq[t] * (double)kk[(size_t)i * d_h + t];
                     s[i] = scale * dot;
                     if (s[i] > smax) smax = s[i];
                 }
                 double z = 0.0;
-                for (int i = 0; i < n; ++i) { s[i] = exp(s[i] - smax); z += s[i]; }
-                for (int i = 0; i < n; ++i) out[i] += s[i] / z;
+                for (int i = 0; i < visible; ++i) { s[i] = exp(s[i] - smax); z += s[i]; }
+                for (int i = 0; i < visible; ++i) out[i] += s[i] / z;
             }
             if (!window_sum)
                 for (int i = 0; i < n; ++i) out[i] /= (double)W;
@@ -187,8 +192,12 @@ int ckvo_projected_value_norm(int b, int H, int Hkv, int d_h, int d_model, int n
  *     attn[bi,g,i] = (1/G) sum_{h in g} abar[bi,h,i]
  *     crit[bi,g,i] = (1/G) sum_{h in g} (abar[bi,h,i] + eps) * N[bi,h,i]
  * With G == 1 this is exactly the paper's A and (A + eps) * ||V W^O||_1.
+ *
+ * protect_last > 0 (the observation-window methods the paper builds on keep the window's own tokens):
+ * the last protect_last entries get both keys set to the largest float32 (FLT_MAX, as a double), so they
+ * are taken first and, being equal, in index order.
  */
-int ckvo_group_keys(int b, int H, int Hkv, int n, double eps,
+int ckvo_group_keys(int b, int H, int Hkv, int n, double eps, int protect_last,
                     const double *abar, const double *N, double *attn, double *crit)
 {
     if (b < 1 || H < 1 || Hkv < 1 || H % Hkv || n < 1) return CKVO_BAD_ARG;
@@ -203,6 +212,7 @@ int ckvo_group_keys(int b, int H, int Hkv, int n, double eps,
                     sa += abar[o];
                     sc += (abar[o] + eps) * N[o];
                 }
+                if (i >= n - protect_last) sa = sc = 3.4028234663852886e38 * (double)G;
                 attn[((size_t)bi * Hkv + g) * (size_t)n + i] = sa / (double)G;
                 crit[((size_t)bi * Hkv + g) * (size_t)n + i] = sc / (double)G;
             }

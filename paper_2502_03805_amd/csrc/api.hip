@@ -21,7 +21,8 @@ static int resolve(const ckv_layer_desc *desc, Dims *out)
     if (c.pool_kernel < 1 || (c.pool_kernel % 2) == 0) return CKV_E_INVALID_ARG;
     if (c.dtype != CKV_BF16 && c.dtype != CKV_F32) return CKV_E_INVALID_ARG;
     if (c.window_reduce != CKV_MEAN && c.window_reduce != CKV_SUM) return CKV_E_INVALID_ARG;
-    if (c.flags & ~(CKV_WO_OUT_IN | CKV_NO_MFMA | CKV_WO_IS_GRAM)) return CKV_E_INVALID_ARG;
+    if (c.flags & ~(CKV_WO_OUT_IN | CKV_NO_MFMA | CKV_WO_IS_GRAM | CKV_CAUSAL_TAIL | CKV_PROTECT_WINDOW))
+        return CKV_E_INVALID_ARG;
     if ((c.flags & CKV_WO_IS_GRAM) && (c.norm != CKV_NORM_L2 || (c.flags & CKV_NO_MFMA))) return CKV_E_INVALID_ARG;
     if (!(c.softmax_scale >= 0.0f) || !isfinite(c.softmax_scale)) return CKV_E_INVALID_ARG;
     if (!(c.eps >= 0.0f) || !isfinite(c.eps)) return CKV_E_INVALID_ARG;
@@ -39,6 +40,8 @@ static int resolve(const ckv_layer_desc *desc, Dims *out)
     d.dh = c.head_dim; d.dm = c.d_model; d.n = c.n_ctx; d.W = c.window; d.pool_k = c.pool_kernel;
     d.window_sum = c.window_reduce == CKV_SUM;
     d.norm = c.norm;
+    d.causal = (c.flags & CKV_CAUSAL_TAIL) ? 1 : 0;
+    d.protect = (c.flags & CKV_PROTECT_WINDOW) ? c.window : 0;
     d.scale = c.softmax_scale > 0.0f ? c.softmax_scale : 1.0f / sqrtf((float)c.head_dim);
     d.eps = c.eps;
     const int64_t contiguous[3] = {(int64_t)d.Hkv * d.n * d.dh, (int64_t)d.n * d.dh, (int64_t)d.dh};

@@ -74,7 +74,7 @@ __device__ __forceinline__ void stage_queries(const T *q, int W, float *q_lds)
 template <typename T, int DH>
 __global__ __launch_bounds__(GEN_THREADS) void attn_stats_generic_kernel(
     const T *__restrict__ q, const T *__restrict__ k, float *__restrict__ part, int H, int G, int n, int W,
-    int chunks, float scale, int64_t ks0, int64_t ks1, int64_t ks2)
+    int chunks, float scale, int64_t ks0, int64_t ks1, int64_t ks2, int causal)
 {
     extern __shared__ float smem[];
     float *q_lds = smem;               // [W][DH]
@@ -85,24 +85,28 @@ __global__ __launch_bounds__(GEN_THREADS) void attn_stats_generic_kernel(
     stage_queries<T, DH>(q + ((size_t)bi * H + h) * (size_t)W * DH, W, q_lds);
     const int i = chunk * GEN_THREADS + threadIdx.x;
     const bool valid = i < n;
+    // with the causal tail, key i is seen by window rows w >= i - (n - W) only
+    const int first_w = causal ? max(0, i - (n - W)) : 0;
     float kr[DH];
     load_row<T, DH>(k + bi * ks0 + g * ks1 + (int64_t)(valid ? i : n - 1) * ks2, kr);
     __syncthreads();
     for (int w = 0; w < W; ++w) {
-        const float s = valid ? scale * dot_lds<DH>(q_lds + w * DH, kr) : -INFINITY;
+        const float s = (valid && w >= first_w) ? scale * dot_lds<DH>(q_lds + w * DH, kr) : -INFINITY;
         const float m = wave_max(s);
         if (lane == 0) red[w * 4 + wave] = m;
     }
     __syncthreads();
     for (int w = 0; w < W; ++w) {
-        const float m = fmaxf(fmaxf(red[w * 4], red[w * 4 + 1]), fmaxf(red[w * 4 + 2], red[w * 4 + 3]));
-        const float s = valid ? scale * dot_lds<DH>(q_lds + w * DH, kr) : -INFINITY;
-        const float e = wave_sum(valid ? __expf(s - m) : 0.f);
+        // a chunk may hold no visible key for this row (max = -inf): its partial sum is 0
+        const float m = fmaxf(fmaxf(fmaxf(red[w * 4], red[w * 4 + 1]), fmaxf(red[w * 4 + 2], red[w * 4 + 3])), -1.0e30f);
+        const bool seen = valid && w >= first_w;
+        const float s = seen ? scale * dot_lds<DH>(q_lds + w * DH, kr) : -INFINITY;
+        const float e = wave_sum(seen ? __expf(s - m) : 0.f);
         if (lane == 0) red[W * 4 + w * 4 + wave] = e;
     }
     __syncthreads();
     for (int w = threadIdx.x; w < W; w += GEN_THREADS) {
-        const float m = fmaxf(fmaxf(red[w * 4], red[w * 4 + 1]), fmaxf(red[w * 4 + 2], red[w * 4 + 3]));
+        const float m = fmaxf(fmaxf(fmaxf(red[w * 4], red[w * 4 + 1]), fmaxf(red[w * 4 + 2], red[w * 4 + 3])), -1.0e30f);
         const float l = red[W * 4 + w * 4] + red[W * 4 + w * 4 + 1] + red[W * 4 + w * 4 + 2] + red[W * 4 + w * 4 + 3];
         float *dst = part + ((((size_t)bi * H + h) * W + w) * (size_t)chunks + chunk) * 2;
         dst[0] = m;
@@ -132,7 +136,7 @@ __global__ __launch_bounds__(64) void attn_stats_reduce_kernel(const float *__re
 template <typename T, int DH>
 __global__ __launch_bounds__(GEN_THREADS) void attn_colsum_generic_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const float *__restrict__ stats, float *__restrict__ a_raw,
-    int H, int G, int n, int W, float scale, int64_t ks0, int64_t ks1, int64_t ks2)
+    int H, int G, int n, int W, float scale, int64_t ks0, int64_t ks1, int64_t ks2, int causal)
 {
     extern __shared__ float smem[];
     float *q_lds = smem;                 // [W][DH]
@@ -147,7 +151,7 @@ __global__ __launch_bounds__(GEN_THREADS) void attn_colsum_generic_kernel(
     load_row<T, DH>(k + bi * ks0 + g * ks1 + (int64_t)(valid ? i : n - 1) * ks2, kr);
     __syncthreads();
     float acc = 0.f;
-    for (int w = 0; w < W; ++w) {
+    for (int w = causal ? max(0, i - (n - W)) : 0; w < W; ++w) {
         const float s = scale * dot_lds<DH>(q_lds + w * DH, kr);
         acc += __expf(s - st[2 * w]) * st[2 * w + 1];
     }
@@ -160,7 +164,7 @@ static hipError_t stats_generic_t(const Dims &d, const void *q, const void *k, f
     const size_t lds = ((size_t)d.W * DH + (size_t)d.W * 8) * sizeof(float);
     dim3 grid(chunks, d.H, d.batch);
     hipLaunchKernelGGL((attn_stats_generic_kernel<T, DH>), grid, dim3(GEN_THREADS), lds, s, (const T *)q, (const T *)k,
-                       part, d.H, d.G, d.n, d.W, chunks, d.scale, d.ks[0], d.ks[1], d.ks[2]);
+                       part, d.H, d.G, d.n, d.W, chunks, d.scale, d.ks[0], d.ks[1], d.ks[2], d.causal);
     return hipGetLastError();
 }
 
@@ -171,7 +175,7 @@ static hipError_t colsum_generic_t(const Dims &d, const void *q, const void *k, 
     const size_t lds = ((size_t)d.W * DH + (size_t)d.W * 2) * sizeof(float);
     dim3 grid((d.n + GEN_THREADS - 1) / GEN_THREADS, d.H, d.batch);
     hipLaunchKernelGGL((attn_colsum_generic_kernel<T, DH>), grid, dim3(GEN_THREADS), lds, s, (const T *)q,
-                       (const T *)k, stats, a_raw, d.H, d.G, d.n, d.W, d.scale, d.ks[0], d.ks[1], d.ks[2]);
+                       (const T *)k, stats, a_raw, d.H, d.G, d.n, d.W, d.scale, d.ks[0], d.ks[1], d.ks[2], d.causal);
     return hipGetLastError();
 }
 

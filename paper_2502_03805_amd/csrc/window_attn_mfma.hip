@@ -40,6 +40,7 @@ struct AttnArgs {
     const bf16_t *q;
     const bf16_t *k;
     int H, G, n, W, chunks;
+    int causal; // window row w sees keys <= n - W + w only
     float c; // scale * log2(e)
     int64_t ks0, ks1, ks2;
 };
@@ -130,7 +131,8 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_stats_mfma_kernel(Attn
             if (key0 >= key_end) break;
             bf16x8 kf[8];
             read_k_frags(cur, kb, l32, half, kf);
-            const bool ragged = key0 + 32 > A.n;
+            // blocks past the end of the keys, or (causal tail) reaching into the last W keys, need masking
+            const bool ragged = key0 + 32 > A.n || (A.causal && key0 + 31 > A.n - A.W);
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
                 f32x16 acc = zero16();
@@ -139,9 +141,12 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_stats_mfma_kernel(Attn
                 // acc[j]: key key0 + 8*(j/4) + 4*half + j%4, query row l32
                 // t = acc * c with c > 0, so the block maximum of t is c * max(acc); 2^(t - m) = 2^fma(acc, c, -m)
                 if (ragged) {
+                    const int last_seen = A.causal ? A.n - A.W + qb * 32 + l32 : A.n - 1; // last key this row sees
 #pragma unroll
-                    for (int j = 0; j < 16; ++j)
-                        if (key0 + 8 * (j / 4) + 4 * half + (j % 4) >= A.n) acc[j] = -INFINITY;
+                    for (int j = 0; j < 16; ++j) {
+                        const int key = key0 + 8 * (j / 4) + 4 * half + (j % 4);
+                        if (key >= A.n || key > last_seen) acc[j] = -INFINITY;
+                    }
                 }
                 float amax = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
 #pragma unroll
@@ -237,12 +242,18 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_colsum_mfma_kernel(Att
             bf16x8 kf[8];
             read_k_frags(cur, kb, l32, half, kf);
             float colsum = 0.f;
+            const bool tail = A.causal && key0 + 31 > A.n - A.W; // some window rows do not see these keys
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
                 f32x16 acc = zero16();
 #pragma unroll
                 for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[qb][s], kf[s], acc, 0, 0, 0);
                 // acc[j]: window row qb*32 + 8*(j/4) + 4*half + j%4, key key0 + l32
+                if (tail) {
+#pragma unroll
+                    for (int j = 0; j < 16; ++j)
+                        if (key0 + l32 > A.n - A.W + qb * 32 + 8 * (j / 4) + 4 * half + (j % 4)) acc[j] = -INFINITY;
+                }
 #pragma unroll
                 for (int j = 0; j < 16; ++j) colsum += __builtin_amdgcn_exp2f(fmaf(acc[j], A.c, -e[qb][j]));
             }
@@ -264,7 +275,7 @@ static AttnArgs make_args(const Dims &d, const void *q, const void *k, int chunk
 {
     AttnArgs A;
     A.q = (const bf16_t *)q; A.k = (const bf16_t *)k;
-    A.H = d.H; A.G = d.G; A.n = d.n; A.W = d.W; A.chunks = chunks;
+    A.H = d.H; A.G = d.G; A.n = d.n; A.W = d.W; A.chunks = chunks; A.causal = d.causal;
     A.c = d.scale * AM_LOG2E;
     A.ks0 = d.ks[0]; A.ks1 = d.ks[1]; A.ks2 = d.ks[2];
     return A;

@@ -48,7 +48,7 @@ class GpuResult:
 
 
 def run_gpu_pass(P, cfg, tensors, budget, alpha, *, flags=0, wo_out_in=False, max_budget=None, want_vnorm=True,
-                 window_reduce=None, softmax_scale=0.0, dev=None, norm=1) -> GpuResult:
+                 window_reduce=None, softmax_scale=0.0, dev=None, norm=1) -> GpuResult:  # flags may carry CKV_CAUSAL_TAIL etc.
     """score -> select -> compact through the C ABI on cuda:0; returns host copies."""
     import torch
     if wo_out_in:

@@ -131,6 +131,68 @@ def test_l2_with_prepared_gram_matches_inline_gram(P):
         assert np.array_equal(res.idx, inline.idx)
 
 
+@pytest.mark.parametrize("path", ["mfma", "valu", "f32"])
+@pytest.mark.parametrize("n", [1000, 257, 70])
+def test_causal_tail_and_protected_window(P, path, n):
+    """Chunked-prefill mode: causal mask inside the window and the window's own tokens always kept."""
+    if path == "f32":
+        cfg = CONFIGS["tiny"].with_(n_ctx=n, budget=max(12, n // 8), window=8)
+    else:
+        cfg = reduced(CONFIGS["llama32k"], n, d_model=256, budget=max(40, n // 5))
+    t = make_layer(cfg)
+    flags = P.CKV_CAUSAL_TAIL | P.CKV_PROTECT_WINDOW | (P.CKV_NO_MFMA if path == "valu" else 0)
+    ref = O.full_pass(t["q_win"], t["k"], t["v"], t["w_o"], cfg.budget, cfg.alpha, pool_kernel=cfg.pool_kernel,
+                      eps=cfg.eps, causal_tail=True, protect_window=True)
+    res = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, flags=flags, wo_out_in=(path != "f32"))
+    W = cfg.window
+    fmax = np.float32(np.finfo(np.float32).max)
+    assert np.all(res.attn[..., -W:] == fmax) and np.all(res.crit[..., -W:] == fmax)
+    assert_scores_close(res.attn[..., :-W], ref.attn[..., :-W], "attn (causal tail)")
+    assert_scores_close(res.crit[..., :-W], ref.crit[..., :-W], "crit (causal tail)")
+    compare_selection(res.idx, res.count, ref, cfg.budget, cfg.alpha)
+    for g in range(cfg.n_kv_heads):
+        assert set(range(n - W, n)) <= set(res.idx[0, g].tolist()), "window tokens must be kept"
+    # each flag alone
+    ref_c = O.full_pass(t["q_win"], t["k"], t["v"], t["w_o"], cfg.budget, cfg.alpha, pool_kernel=cfg.pool_kernel,
+                        eps=cfg.eps, causal_tail=True)
+    res_c = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, flags=flags & ~P.CKV_PROTECT_WINDOW, wo_out_in=(path != "f32"))
+    assert_scores_close(res_c.attn, ref_c.attn, "attn (causal only)")
+    compare_selection(res_c.idx, res_c.count, ref_c, cfg.budget, cfg.alpha)
+
+
+def test_chunked_prefill_loop_matches_oracle_loop(P):
+    """Three chunks of a prompt with eviction after each: the GPU host loop and the same loop over the oracle
+    keep the same entries and end with the same cache."""
+    import torch
+    from paper_2502_03805_amd.chunked import chunked_prefill_evict
+    base = reduced(CONFIGS["llama32k"], 3 * 700, d_model=256)
+    t = make_layer(base)
+    chunk, budget, alpha = 700, 500, 0.5
+    qs = [make_layer(base.with_(n_ctx=64), seed_offset=10 + c)["q_win"] for c in range(3)]
+    ks = [t["k"][:, :, c * chunk:(c + 1) * chunk] for c in range(3)]
+    vs = [t["v"][:, :, c * chunk:(c + 1) * chunk] for c in range(3)]
+    # oracle loop
+    kc = vc = None
+    kept_ref = []
+    for c in range(3):
+        k_all = ks[c] if kc is None else np.concatenate([kc, ks[c]], axis=2)
+        v_all = vs[c] if vc is None else np.concatenate([vc, vs[c]], axis=2)
+        r = O.full_pass(qs[c], k_all, v_all, t["w_o"], budget, alpha, pool_kernel=base.pool_kernel, eps=base.eps,
+                        causal_tail=True, protect_window=True)
+        kc, vc = r.k_out, r.v_out
+        kept_ref.append(r.idx)
+    # GPU loop
+    dev = to_device(base, t, True)
+    tb = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda", torch.bfloat16)
+    mk = lambda n: cfg_desc(P, base.with_(n_ctx=n), flags=P.CKV_WO_OUT_IN | P.CKV_CAUSAL_TAIL | P.CKV_PROTECT_WINDOW)
+    k_cache, v_cache, kept = chunked_prefill_evict(mk, [tb(q) for q in qs], [tb(k) for k in ks], [tb(v) for v in vs],
+                                                   dev["w_o"], budget, alpha)
+    torch.cuda.synchronize()
+    for c in range(3):
+        assert np.array_equal(kept[c].cpu().numpy(), kept_ref[c]), f"chunk {c}: kept sets differ"
+    assert np.array_equal(k_cache.float().cpu().numpy(), kc) and np.array_equal(v_cache.float().cpu().numpy(), vc)
+
+
 def test_window_sum_and_explicit_scale(P):
     cfg = reduced(CONFIGS["llama32k"], 900, d_model=256)
     t = make_layer(cfg)

@@ -75,6 +75,46 @@ def test_window_attention_scale_and_shift_invariance():
     np.testing.assert_allclose(a3, a2, rtol=tol)
 
 
+def test_causal_tail_matches_explicitly_masked_softmax():
+    r = rng(5)
+    H, Hkv, n, dh, W = 4, 2, 29, 8, 6
+    q = r.standard_normal((1, H, W, dh)).astype(np.float32)
+    k = r.standard_normal((1, Hkv, n, dh)).astype(np.float32)
+    a = O.window_attention(q, k, causal_tail=True)
+    for h in range(H):
+        logits = q[0, h].astype(np.float64) @ k[0, h // 2].astype(np.float64).T / np.sqrt(dh)   # [W, n]
+        pos = n - W + np.arange(W)[:, None]
+        masked = np.where(np.arange(n)[None, :] <= pos, logits, -np.inf)
+        ref = scipy.special.softmax(masked, axis=1).mean(axis=0)
+        np.testing.assert_allclose(a[0, h], ref, rtol=1e-12, atol=1e-300)
+    # the last key is visible to the last window row only: its weight is at most 1/W
+    assert np.all(a[0, :, -1] <= 1.0 / W + 1e-15) and np.all(a[0, :, -1] > 0)
+    # without the flag nothing is masked; W = n, W = 1 corner cases run
+    full = O.window_attention(q, k)
+    assert not np.allclose(full, a)
+    one = O.window_attention(q[:, :, :1], k, causal_tail=True)
+    np.testing.assert_allclose(one, O.window_attention(q[:, :, :1], k), rtol=1e-13)
+
+
+def test_protected_window_entries_are_always_selected():
+    r = rng(6)
+    b, H, Hkv, n, W = 1, 4, 2, 40, 5
+    abar = r.random((b, H, n))
+    N = r.random((b, H, n))
+    attn, crit = O.group_keys(abar, N, Hkv, 1e-4, protect_last=W)
+    assert np.all(attn[..., -W:] == np.float64(np.finfo(np.float32).max)) and np.all(crit[..., -W:] == attn[..., -W:])
+    base_attn, base_crit = O.group_keys(abar, N, Hkv, 1e-4)
+    np.testing.assert_array_equal(attn[..., :-W], base_attn[..., :-W])
+    for B in (W, W + 3, 20):
+        for alpha in (0.0, 0.5, 1.0):
+            idx, count, _ = O.select(attn, crit, B, alpha)
+            for g in range(Hkv):
+                assert set(range(n - W, n)) <= set(idx[0, g].tolist())
+    # a budget below the window keeps the first window tokens (equal keys: index order)
+    idx, _, _ = O.select(attn, crit, 3, 0.5)
+    assert idx[0, 0].tolist() == [n - W, n - W + 1, n - W + 2]
+
+
 def test_theorem_3_2_masked_softmax_identity():
     """A' = (N . A) / sum(N A) equals the softmax with -inf on the evicted logits (Theorem 3.2)."""
     r = rng(4)
