@@ -76,8 +76,9 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the steps are issued on round-robin (independent layers overlap); 1 = serial")
-    ap.add_argument("--norm", choices=["l1", "l2"], default="l1",
-                    help="l1: the paper's default (dense d_model-wide projection); l2: the L2 variant via the Gram matrix")
+    ap.add_argument("--norm", choices=["l1", "l2", "none"], default="l1",
+                    help="l1: the paper's default (dense d_model-wide projection); l2: the L2 variant via the Gram "
+                         "matrix; none: attention-only baseline selection (no projected magnitude)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale profiler byte counters)")
     args = ap.parse_args()
@@ -101,7 +102,8 @@ def main():
     # rotate enough input sets that K and V of consecutive steps cannot sit in the 256 MB Infinity Cache
     nsets = args.sets or max(2, min(4, int(np.ceil(512e6 / kv_bytes))))
     l2 = args.norm == "l2"
-    desc = cfg_desc(P, cfg, flags=P.CKV_WO_IS_GRAM if l2 else P.CKV_WO_OUT_IN, norm=P.CKV_NORM_L2 if l2 else P.CKV_NORM_L1)
+    flags = P.CKV_WO_IS_GRAM if l2 else (P.CKV_ATTN_ONLY if args.norm == "none" else P.CKV_WO_OUT_IN)
+    desc = cfg_desc(P, cfg, flags=flags, norm=P.CKV_NORM_L2 if l2 else P.CKV_NORM_L1)
     B = cfg.budget
     sets = []
     host0 = None
@@ -186,7 +188,7 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     vproj_ms = [ev.ms(ctypes.c_void_p(a[vslot]), ctypes.c_void_p(a[vslot + 1])) for a in step_events]
-    vproj_avg = float(np.mean(vproj_ms))
+    vproj_avg = max(float(np.mean(vproj_ms)), 1e-6)
     for lane in lanes[:min(n_streams, args.steps)]:
         assert int(lane["count"].min()) == B and int(lane["count"].max()) == B
 
@@ -229,7 +231,7 @@ def main():
     value = entries / (ms_per_step * 1e-3) / 1e6
     # L1: the d_h x d_model projection per query head.  L2: v G v^T with the d_h x d_h Gram matrix (the split of
     # G into two bf16 matrices doubles the MFMA work actually issued; the algorithmic count does not include it)
-    flops = 2.0 * b * H * n * dh * (dm if args.norm == "l1" else dh)
+    flops = 2.0 * b * H * n * dh * (dm if args.norm == "l1" else dh if l2 else 0)
     achieved = flops / (vproj_avg * 1e-3) / 1e12
     # lower bound of the whole pass: K and V read once, W_O once, the MFMA contraction, the gather traffic
     hbm_bytes = (kv_bytes                      # K and V read once
@@ -265,8 +267,15 @@ def main():
         sample = {k: (v[:, :, :ns] if k in ("k", "v") else v) for k, v in host0.items()}
         O.lib()
         c0 = time.perf_counter()
-        O.full_pass(sample["q_win"], sample["k"], sample["v"], sample["w_o"], Bs, cfg.alpha,
-                    pool_kernel=cfg.pool_kernel, eps=cfg.eps, norm=2 if args.norm == "l2" else 1)
+        if args.norm == "none":
+            a = O.maxpool1d(O.window_attention(sample["q_win"], sample["k"]), cfg.pool_kernel)
+            at, _ = O.group_keys(a, np.zeros_like(a), Hkv, cfg.eps)
+            ix, ct, _ = O.select(at, at, Bs, 1.0)
+            O.compact(sample["k"], ix, ct)
+            O.compact(sample["v"], ix, ct)
+        else:
+            O.full_pass(sample["q_win"], sample["k"], sample["v"], sample["w_o"], Bs, cfg.alpha,
+                        pool_kernel=cfg.pool_kernel, eps=cfg.eps, norm=2 if l2 else 1)
         c1 = time.perf_counter()
         out["cpu_baseline"] = {"value": round(b * Hkv * ns / (c1 - c0) / 1e6, 4), "unit": "M KV entries/s",
                                "cores": O.num_threads(), "kind": "oracle",

@@ -73,6 +73,9 @@ extern "C" {
                             without it every window row sees all n keys (the algorithm as printed)    */
 #define CKV_PROTECT_WINDOW 16u /* the last W entries (the window's own tokens) are always kept while the
                             budget allows: their attn and crit are set to FLT_MAX (ties: index order)   */
+#define CKV_ATTN_ONLY 32u /* baseline: skip the projected-value magnitude; crit is set equal to attn, so the
+                            selection is attention-only Top-B for every alpha (Algorithm 2's regular
+                            selection).  w_o and v are not read by criticalkv_score (may be NULL).      */
 #define CKV_WO_IS_GRAM 4u /* CKV_NORM_L2 only: the w_o argument of criticalkv_score is the per-layer
                             constant written by criticalkv_prepare_gram, not the projection itself  */
 

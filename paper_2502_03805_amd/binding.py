@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("CRITICALKV_LIB") or os.path.join(PKG, "libcriticalkv.
 CKV_BF16, CKV_F32 = 0, 1
 CKV_NORM_L1, CKV_NORM_L2 = 1, 2
 CKV_MEAN, CKV_SUM = 0, 1
-CKV_WO_OUT_IN, CKV_NO_MFMA, CKV_WO_IS_GRAM, CKV_CAUSAL_TAIL, CKV_PROTECT_WINDOW = 1, 2, 4, 8, 16
+CKV_WO_OUT_IN, CKV_NO_MFMA, CKV_WO_IS_GRAM, CKV_CAUSAL_TAIL, CKV_PROTECT_WINDOW, CKV_ATTN_ONLY = 1, 2, 4, 8, 16, 32
 CKV_OK, CKV_E_INVALID_ARG, CKV_E_UNSUPPORTED, CKV_E_WORKSPACE, CKV_E_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("criticalkv_workspace_bytes", "criticalkv_score", "criticalkv_score_profiled", "criticalkv_select",

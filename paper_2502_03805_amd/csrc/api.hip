@@ -21,7 +21,7 @@ static int resolve(const ckv_layer_desc *desc, Dims *out)
     if (c.pool_kernel < 1 || (c.pool_kernel % 2) == 0) return CKV_E_INVALID_ARG;
     if (c.dtype != CKV_BF16 && c.dtype != CKV_F32) return CKV_E_INVALID_ARG;
     if (c.window_reduce != CKV_MEAN && c.window_reduce != CKV_SUM) return CKV_E_INVALID_ARG;
-    if (c.flags & ~(CKV_WO_OUT_IN | CKV_NO_MFMA | CKV_WO_IS_GRAM | CKV_CAUSAL_TAIL | CKV_PROTECT_WINDOW))
+    if (c.flags & ~(CKV_WO_OUT_IN | CKV_NO_MFMA | CKV_WO_IS_GRAM | CKV_CAUSAL_TAIL | CKV_PROTECT_WINDOW | CKV_ATTN_ONLY))
         return CKV_E_INVALID_ARG;
     if ((c.flags & CKV_WO_IS_GRAM) && (c.norm != CKV_NORM_L2 || (c.flags & CKV_NO_MFMA))) return CKV_E_INVALID_ARG;
     if (!(c.softmax_scale >= 0.0f) || !isfinite(c.softmax_scale)) return CKV_E_INVALID_ARG;
@@ -109,10 +109,12 @@ static int score_impl(const ckv_layer_desc *desc, const void *q_win, const void 
     Dims d;
     int rc = resolve(desc, &d);
     if (rc != CKV_OK) return rc;
-    if (!q_win || !k || !v || !w_o || !attn || !crit) return CKV_E_INVALID_ARG;
+    const bool attn_only = desc->flags & CKV_ATTN_ONLY;
+    if (!q_win || !k || !attn || !crit || (!attn_only && (!v || !w_o))) return CKV_E_INVALID_ARG;
+    if (attn_only && vnorm_opt) return CKV_E_INVALID_ARG; // no magnitudes are computed in this mode
     const bool have_gram = desc->flags & CKV_WO_IS_GRAM;
     if (have_gram && !(mfma_allowed(desc) && vproj_l2_mfma_supported(d))) return CKV_E_UNSUPPORTED;
-    const bool need_wt = !have_gram && !(desc->flags & CKV_WO_OUT_IN);
+    const bool need_wt = !attn_only && !have_gram && !(desc->flags & CKV_WO_OUT_IN);
     const Workspace ws = carve_workspace(d, desc->dtype, need_wt);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
 
@@ -150,7 +152,10 @@ static int score_impl(const ckv_layer_desc *desc, const void *q_win, const void 
     if (e != hipSuccess) return CKV_E_HIP;
     mark(ev, 2 * CKV_STAGE_ATTN_COLSUM + 1, s);
     mark(ev, 2 * CKV_STAGE_VPROJ, s);
-    if (d.norm == CKV_NORM_L2 && mfma_allowed(desc) && vproj_l2_mfma_supported(d)) {
+    if (attn_only) {
+        e = hipSuccess;
+        vnorm = nullptr; // combine then writes crit = attn
+    } else if (d.norm == CKV_NORM_L2 && mfma_allowed(desc) && vproj_l2_mfma_supported(d)) {
         const void *gram = w_o; // prepared by the caller, or computed here from the projection
         if (!have_gram) {
             char *scratch = base + ws.l2_scratch;

@@ -3,7 +3,7 @@
 //
 //   abar^h_i = max{ a^h_j : |j - i| <= pool_k/2, 0 <= j < n }
 //   attn[g,i] = (1/G) sum_{h in g} abar^h_i
-//   crit[g,i] = (1/G) sum_{h in g} (abar^h_i + eps) * N^h_i
+//   crit[g,i] = (1/G) sum_{h in g} (abar^h_i + eps) * N^h_i      (= attn[g,i] when no magnitudes are given)
 // Every output is computed by the same sequence of fp32 operations on its inputs, so
 // entries whose pooled scores are equal get bitwise equal keys (ties stay ties).
 #include "common.hpp"
@@ -36,7 +36,7 @@ __global__ __launch_bounds__(CB_THREADS) void combine_kernel(const float *__rest
         for (int r = 1; r <= 2 * radius; ++r) m = fmaxf(m, tile[threadIdx.x + r]);
         if (i < n) {
             sum_a += m;
-            sum_c += (m + eps) * vnorm[row + i];
+            sum_c += vnorm ? (m + eps) * vnorm[row + i] : m; // no magnitudes: crit = attn
         }
     }
     if (i < n) {

@@ -193,6 +193,37 @@ def test_chunked_prefill_loop_matches_oracle_loop(P):
     assert np.array_equal(k_cache.float().cpu().numpy(), kc) and np.array_equal(v_cache.float().cpu().numpy(), vc)
 
 
+def test_attention_only_baseline_mode(P):
+    """CKV_ATTN_ONLY: no projected magnitude; crit == attn and the selection is attention-only Top-B
+    (Algorithm 2's regular selection) for every alpha."""
+    import torch
+    cfg = reduced(CONFIGS["llama32k"], 3000, d_model=256)
+    t = make_layer(cfg)
+    a = O.maxpool1d(O.window_attention(t["q_win"], t["k"]), cfg.pool_kernel)
+    attn_ref, _ = O.group_keys(a, np.zeros_like(a), cfg.n_kv_heads, cfg.eps)
+    desc = cfg_desc(P, cfg, flags=P.CKV_ATTN_ONLY)
+    dev = to_device(cfg, t, False)
+    b, Hkv, n = cfg.batch, cfg.n_kv_heads, cfg.n_ctx
+    ws = torch.empty(P.workspace_bytes(desc, cfg.budget), dtype=torch.uint8, device="cuda")
+    attn = torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda")
+    crit = torch.empty_like(attn)
+    P.criticalkv_score(desc, dev["q_win"], dev["k"], None, None, attn, crit, None, workspace=ws)
+    idx = torch.empty((b, Hkv, cfg.budget), dtype=torch.int32, device="cuda")
+    count = torch.empty((b, Hkv), dtype=torch.int32, device="cuda")
+    bud = torch.full((b, Hkv), cfg.budget, dtype=torch.int32, device="cuda")
+    got = {}
+    for alpha in (0.0, 0.5, 1.0):
+        P.criticalkv_select(desc, attn, crit, bud, alpha, cfg.budget, idx, count, workspace=ws)
+        torch.cuda.synchronize()
+        got[alpha] = idx.cpu().numpy().copy()
+    assert torch.equal(attn, crit)
+    assert_scores_close(attn.cpu().numpy(), attn_ref, "attn (attention-only)")
+    a32 = attn.cpu().numpy().astype(np.float64)
+    ref_idx, _, _ = O.select(a32, a32, cfg.budget, 1.0)
+    for alpha in got:
+        assert np.array_equal(got[alpha], ref_idx)
+
+
 def test_window_sum_and_explicit_scale(P):
     cfg = reduced(CONFIGS["llama32k"], 900, d_model=256)
     t = make_layer(cfg)
