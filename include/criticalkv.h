@@ -104,8 +104,8 @@ typedef struct ckv_layer_desc {
 } ckv_layer_desc;
 
 /*
- * Bytes of workspace that criticalkv_score and criticalkv_select need for this layer
- * (the larger of the two; compact needs none).  Returns 0 if the descriptor is invalid.
+ * Bytes of workspace that criticalkv_score, criticalkv_select and criticalkv_allocate need for this
+ * layer (the largest of them; compact needs none).  max_budget only sizes criticalkv_allocate's list.  Returns 0 if the descriptor is invalid.
  * Host-only computation.
  */
 CKV_API size_t criticalkv_workspace_bytes(const ckv_layer_desc *desc, int32_t max_budget);
@@ -181,6 +181,28 @@ CKV_API int criticalkv_score_profiled(const ckv_layer_desc *desc, const void *q_
 CKV_API int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float *crit,
                               const int32_t *budget, float alpha, int32_t max_budget, int32_t *idx,
                               int32_t *count, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Per-head budgets from a per-batch-item total (the allocation step of Algorithm 2 line 1).
+ *
+ * The paper names this step and cites adaptive allocation methods without defining one; the rule here is
+ * this library's own, in the spirit of those methods:
+ *   f  = floor(floor_frac * total_budget / Hkv) (in double)     every head's floor
+ *   P  = total_budget - Hkv * f                                  slots handed out by score
+ *   T  = the P entries with the largest attn among all Hkv * n entries of the batch item
+ *        (equal scores: the lower kv head, then the lower token, first)
+ *   budget[bi,g] = min(n, f + #{entries of T owned by head g})
+ * floor_frac = 1 gives the uniform split, floor_frac = 0 a purely score-driven one.
+ *
+ * in : attn [batch, Hkv, n] float32 contiguous (criticalkv_score's pooled attention output), DEVICE
+ *      total_budget in [0, Hkv * n], floor_frac in [0, 1]
+ * out: budget [batch, Hkv] int32, DEVICE; feed it to criticalkv_select
+ * workspace: criticalkv_workspace_bytes(desc, max_budget) bytes with Hkv * max_budget >= P always
+ *      suffice; too few bytes give CKV_E_WORKSPACE.  Hkv * n must fit an int32 (CKV_E_UNSUPPORTED).
+ */
+CKV_API int criticalkv_allocate(const ckv_layer_desc *desc, const float *attn, int32_t total_budget,
+                                float floor_frac, int32_t *budget, void *workspace, size_t workspace_bytes,
+                                void *hip_stream);
 
 /*
  * Compacted cache (Algorithm 1 line 10):  k_out[bi,g,j,:] = k[bi,g,idx[bi,g,j],:] for j < count[bi,g],

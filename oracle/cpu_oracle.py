@@ -155,6 +155,17 @@ def select_head(attn, crit, B: int, alpha: float):
     return idx[:B], flag[:B].astype(bool), tau
 
 
+def allocate(attn, total: int, floor_frac: float) -> np.ndarray:
+    """Per-head budgets [b,Hkv] from a per-batch-item total (this build's definition of Algorithm 2 line 1)."""
+    attn, ap = _f64(attn)
+    b, Hkv, n = attn.shape
+    budget = np.zeros((b, Hkv), dtype=np.int32)
+    rc = lib().ckvo_allocate(b, Hkv, n, ap, int(total), ctypes.c_double(float(floor_frac)),
+                             budget.ctypes.data_as(ctypes.POINTER(ctypes.c_int)))
+    _check(rc, "allocate")
+    return budget
+
+
 def compact(src, idx, count) -> np.ndarray:
     """out[b,Hkv,max_budget,d_h]; rows j >= count are zero-filled here (the C routine leaves them)."""
     src, sp = _f32(src)

@@ -309,6 +309,37 @@ int ckvo_select(int heads, int n, const double *attn, const double *crit, const 
 }
 
 /*
+ * Budget allocation across the kv heads of one batch item (Algorithm 2, line 1).
+ *
+ * The paper only names this step (it cites adaptive allocation methods without defining them), so this is
+ * a definition written for this build, in the spirit of the adaptive scheme it cites: every head gets a
+ * floor f = floor(floor_frac * total / Hkv); the remaining P = total - Hkv * f slots go to the P entries
+ * with the largest pooled score `attn` among ALL Hkv * n entries of the batch item (equal scores: lower
+ * head, then lower token first), and a head's budget is f plus the number of those entries it owns,
+ * capped at n.  floor_frac = 1 gives the uniform split.
+ */
+int ckvo_allocate(int b, int Hkv, int n, const double *attn, int total, double floor_frac, int *budget)
+{
+    if (b < 1 || Hkv < 1 || n < 1 || total < 0 || (long long)total > (long long)Hkv * n) return CKVO_BAD_ARG;
+    if (!(floor_frac >= 0.0) || !(floor_frac <= 1.0)) return CKVO_BAD_ARG;
+    const int f = (int)floor(floor_frac * (double)total / (double)Hkv);
+    const int P = total - Hkv * f;
+    const size_t m = (size_t)Hkv * n;
+    ckvo_pair *p = (ckvo_pair *)malloc(sizeof(ckvo_pair) * m);
+    if (!p) return CKVO_NO_MEM;
+    for (int bi = 0; bi < b; ++bi) {
+        for (size_t e = 0; e < m; ++e) { p[e].key = attn[(size_t)bi * m + e]; p[e].idx = (int)e; }
+        qsort(p, m, sizeof(ckvo_pair), ckvo_cmp_desc);
+        for (int g = 0; g < Hkv; ++g) budget[bi * Hkv + g] = f;
+        for (int j = 0; j < P; ++j) budget[bi * Hkv + p[j].idx / n] += 1;
+        for (int g = 0; g < Hkv; ++g)
+            if (budget[bi * Hkv + g] > n) budget[bi * Hkv + g] = n;
+    }
+    free(p);
+    return CKVO_OK;
+}
+
+/*
  * Compacted cache (Algorithm 1, line 10): out[hd, j, :] = src[hd, idx[hd, j], :] for
  * j < count[hd]; later rows are left untouched.  src [heads, n, d_h] float32.
  */

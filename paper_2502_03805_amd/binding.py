@@ -22,7 +22,8 @@ CKV_WO_OUT_IN, CKV_NO_MFMA, CKV_WO_IS_GRAM, CKV_CAUSAL_TAIL, CKV_PROTECT_WINDOW,
 CKV_OK, CKV_E_INVALID_ARG, CKV_E_UNSUPPORTED, CKV_E_WORKSPACE, CKV_E_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("criticalkv_workspace_bytes", "criticalkv_score", "criticalkv_score_profiled", "criticalkv_select",
-           "criticalkv_compact", "criticalkv_strerror", "criticalkv_gram_bytes", "criticalkv_prepare_gram")
+           "criticalkv_compact", "criticalkv_strerror", "criticalkv_gram_bytes", "criticalkv_prepare_gram",
+           "criticalkv_allocate")
 STAGES = ("wo_layout", "attn_stats", "attn_colsum", "vproj", "combine")
 
 
@@ -89,6 +90,8 @@ def load() -> ctypes.CDLL:
         lib.criticalkv_prepare_gram.argtypes = [dp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.criticalkv_select.restype = ctypes.c_int
         lib.criticalkv_select.argtypes = [dp, vp, vp, vp, f32, i32, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.criticalkv_allocate.restype = ctypes.c_int
+        lib.criticalkv_allocate.argtypes = [dp, vp, i32, f32, vp, vp, ctypes.c_size_t, vp]
         lib.criticalkv_compact.restype = ctypes.c_int
         lib.criticalkv_compact.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp]
         lib.criticalkv_strerror.restype = ctypes.c_char_p
@@ -164,6 +167,14 @@ def criticalkv_select(desc: LayerDesc, attn, crit, budget, alpha: float, max_bud
                                   workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != CKV_OK:
         raise CriticalKVError(rc, "criticalkv_select")
+
+
+def criticalkv_allocate(desc: LayerDesc, attn, total_budget: int, floor_frac: float, budget, *, workspace,
+                        stream=None) -> None:
+    rc = load().criticalkv_allocate(ctypes.byref(desc), _ptr(attn), int(total_budget), float(floor_frac), _ptr(budget),
+                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != CKV_OK:
+        raise CriticalKVError(rc, "criticalkv_allocate")
 
 
 def criticalkv_compact(desc: LayerDesc, k, v, idx, count, max_budget: int, k_out, v_out, *, stream=None) -> None:

@@ -1,6 +1,7 @@
 // Host side of the C ABI: argument validation, workspace carving, kernel dispatch.
 // Nothing here computes any part of the pass; every step runs in the gfx950 kernels.
 #include <math.h>
+#include <algorithm>
 
 #include "common.hpp"
 
@@ -59,7 +60,7 @@ static int resolve(const ckv_layer_desc *desc, Dims *out)
     return CKV_OK;
 }
 
-Workspace carve_workspace(const Dims &d, int dtype, bool need_wt)
+Workspace carve_workspace(const Dims &d, int dtype, bool need_wt, int max_budget)
 {
     Workspace w;
     size_t off = 0;
@@ -73,6 +74,8 @@ Workspace carve_workspace(const Dims &d, int dtype, bool need_wt)
     w.l2_scratch = off; if (d.norm == CKV_NORM_L2 && d.dh == 128) off = align256(off + vproj_l2_workspace_bytes(d));
     w.sel_keys = off; off = align256(off + (size_t)d.batch * d.Hkv * d.n * 4);
     w.sel_scratch = off; off = align256(off + select_workspace_words(d.batch * d.Hkv, d.n) * 4);
+    // last, so that the offsets above do not depend on max_budget
+    w.alloc_tmp = off; off = align256(off + ((size_t)2 * d.batch + (size_t)d.batch * d.Hkv * (max_budget > 0 ? max_budget : 0)) * 4);
     w.total = off;
     return w;
 }
@@ -94,7 +97,7 @@ size_t criticalkv_workspace_bytes(const ckv_layer_desc *desc, int32_t max_budget
     if (resolve(desc, &d) != CKV_OK || max_budget < 0) return 0;
     // sized for either w_o layout and either norm so that one allocation serves every call on this layer
     d.norm = CKV_NORM_L2;
-    return carve_workspace(d, desc->dtype, true).total;
+    return carve_workspace(d, desc->dtype, true, max_budget).total;
 }
 
 static void mark(void *const *ev, int slot, hipStream_t s)
@@ -115,7 +118,7 @@ static int score_impl(const ckv_layer_desc *desc, const void *q_win, const void 
     const bool have_gram = desc->flags & CKV_WO_IS_GRAM;
     if (have_gram && !(mfma_allowed(desc) && vproj_l2_mfma_supported(d))) return CKV_E_UNSUPPORTED;
     const bool need_wt = !attn_only && !have_gram && !(desc->flags & CKV_WO_OUT_IN);
-    const Workspace ws = carve_workspace(d, desc->dtype, need_wt);
+    const Workspace ws = carve_workspace(d, desc->dtype, need_wt, 0);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
 
     hipStream_t s = (hipStream_t)hip_stream;
@@ -210,7 +213,7 @@ int criticalkv_prepare_gram(const ckv_layer_desc *desc, const void *w_o, void *g
     if (desc->dtype != CKV_BF16 || !vproj_l2_mfma_supported(d)) return CKV_E_UNSUPPORTED;
     d.norm = CKV_NORM_L2; // the carve below must contain the Gram scratch whatever norm the descriptor names
     const bool need_wt = !(desc->flags & CKV_WO_OUT_IN);
-    const Workspace ws = carve_workspace(d, desc->dtype, need_wt);
+    const Workspace ws = carve_workspace(d, desc->dtype, need_wt, 0);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     char *base = (char *)workspace;
@@ -232,12 +235,34 @@ int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float
     if (!attn || !crit || !budget || !idx || !count) return CKV_E_INVALID_ARG;
     if (!(alpha >= 0.0f) || !(alpha <= 1.0f)) return CKV_E_INVALID_ARG;
     if (max_budget < 1 || max_budget > d.n) return CKV_E_INVALID_ARG;
-    const Workspace ws = carve_workspace(d, desc->dtype, false);
+    const Workspace ws = carve_workspace(d, desc->dtype, false, 0);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
     uint32_t *keys2 = (uint32_t *)((char *)workspace + ws.sel_keys);
     uint32_t *scratch = (uint32_t *)((char *)workspace + ws.sel_scratch);
     hipError_t e = launch_select(d, attn, crit, budget, alpha, max_budget, idx, count, keys2, scratch,
                                  (hipStream_t)hip_stream);
+    return e == hipSuccess ? CKV_OK : CKV_E_HIP;
+}
+
+int criticalkv_allocate(const ckv_layer_desc *desc, const float *attn, int32_t total_budget, float floor_frac,
+                        int32_t *budget, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Dims d;
+    int rc = resolve(desc, &d);
+    if (rc != CKV_OK) return rc;
+    if (!attn || !budget) return CKV_E_INVALID_ARG;
+    if (total_budget < 0 || !(floor_frac >= 0.0f) || !(floor_frac <= 1.0f)) return CKV_E_INVALID_ARG;
+    if ((int64_t)d.Hkv * d.n > (int64_t)INT32_MAX) return CKV_E_UNSUPPORTED;
+    if ((int64_t)total_budget > (int64_t)d.Hkv * d.n) return CKV_E_INVALID_ARG;
+    const int floor_each = (int)floor((double)floor_frac * (double)total_budget / (double)d.Hkv);
+    const int64_t pool = std::min<int64_t>((int64_t)total_budget - (int64_t)d.Hkv * floor_each, (int64_t)d.Hkv * d.n);
+    const int per_head = (int)((pool + d.Hkv - 1) / d.Hkv);
+    const Workspace ws = carve_workspace(d, desc->dtype, false, per_head);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
+    uint32_t *keys2 = (uint32_t *)((char *)workspace + ws.sel_keys);
+    uint32_t *scratch = (uint32_t *)((char *)workspace + ws.sel_scratch);
+    int32_t *tmp = (int32_t *)((char *)workspace + ws.alloc_tmp);
+    hipError_t e = launch_allocate(d, attn, total_budget, floor_frac, budget, keys2, scratch, tmp, (hipStream_t)hip_stream);
     return e == hipSuccess ? CKV_OK : CKV_E_HIP;
 }
 

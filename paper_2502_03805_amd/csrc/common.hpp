@@ -36,6 +36,7 @@ struct Workspace {
     size_t w_t;        // [d_model, H*dh] copy of W_O in output-major layout (when given canonical)
     size_t sel_keys;   // [batch*Hkv, n] u32: stage-2 keys with stage-1 entries marked
     size_t l2_scratch; // Gram partial sums and the split bf16 Gram matrices (L2 norm only)
+    size_t alloc_tmp;  // budget allocation: pool budgets, counts and the pooled index list
     size_t sel_scratch; // digit histograms, per-head state, per-slice counts of the selection kernels
     size_t total;
     int max_chunks;    // capacity of stats_part per window row
@@ -47,7 +48,7 @@ int mfma_attn_chunks(const Dims &d);
 bool attn_mfma_supported(const Dims &d);  // shapes the matrix-core attention kernels cover
 bool vproj_mfma_supported(const Dims &d); // shapes the matrix-core projection kernel covers
 
-Workspace carve_workspace(const Dims &d, int dtype, bool need_wt);
+Workspace carve_workspace(const Dims &d, int dtype, bool need_wt, int max_budget);
 
 // ---- kernel launchers (each returns hipGetLastError after its launches) -------------------------
 // window attention, pass 1: per (row, key chunk) running max and sum of exp
@@ -84,6 +85,9 @@ size_t select_workspace_words(int heads, int n); // u32 words of histogram / sta
 hipError_t launch_select(const Dims &d, const float *attn, const float *crit, const int32_t *budget, float alpha,
                          int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2, uint32_t *scratch,
                          hipStream_t s);
+// per-head budgets from a per-batch-item total; tmp holds 2 * batch + batch * total int32
+hipError_t launch_allocate(const Dims &d, const float *attn, int total, float floor_frac, int32_t *budget_out,
+                           uint32_t *keys2, uint32_t *scratch, int32_t *tmp, hipStream_t s);
 hipError_t launch_compact(const Dims &d, int dtype, const void *k, const void *v, const int32_t *idx,
                           const int32_t *count, int max_budget, void *k_out, void *v_out, hipStream_t s);
 

@@ -400,11 +400,11 @@ size_t select_workspace_words(int heads, int n)
     return (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS) + (size_t)heads * 3 * n_slices;
 }
 
-hipError_t launch_select(const Dims &d, const float *attn, const float *crit, const int32_t *budget, float alpha,
-                         int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2, uint32_t *scratch,
-                         hipStream_t s)
+// heads rows of n keys each (a row is one (batch item, kv head), or one whole batch item for the allocation)
+hipError_t launch_select_rows(int heads, int n, const float *attn, const float *crit, const int32_t *budget,
+                              float alpha, int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2,
+                              uint32_t *scratch, hipStream_t s)
 {
-    const int heads = d.batch * d.Hkv;
     SelArgs A;
     A.attn = reinterpret_cast<const uint32_t *>(attn);
     A.crit = reinterpret_cast<const uint32_t *>(crit);
@@ -415,8 +415,8 @@ hipError_t launch_select(const Dims &d, const float *attn, const float *crit, co
     A.slices = A.state + (size_t)heads * 2 * ST_WORDS;
     A.idx = idx; A.count = count;
     A.alpha = (double)alpha;
-    A.n = d.n; A.max_budget = max_budget;
-    A.n_slices = (d.n + SEL_SLICE - 1) / SEL_SLICE;
+    A.n = n; A.max_budget = max_budget;
+    A.n_slices = (n + SEL_SLICE - 1) / SEL_SLICE;
     const size_t zero_words = (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS);
     dim3 grid(A.n_slices, heads), block(SEL_THREADS);
     hipLaunchKernelGGL(select_zero_kernel, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, s, scratch, zero_words);
@@ -429,6 +429,60 @@ hipError_t launch_select(const Dims &d, const float *attn, const float *crit, co
     hipLaunchKernelGGL((select_hist_kernel<1, 2>), grid, block, 0, s, A);
     hipLaunchKernelGGL(select_count_kernel<1>, grid, block, 0, s, A);
     hipLaunchKernelGGL(select_write_kernel, grid, block, 0, s, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_select(const Dims &d, const float *attn, const float *crit, const int32_t *budget, float alpha,
+                         int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2, uint32_t *scratch,
+                         hipStream_t s)
+{
+    return launch_select_rows(d.batch * d.Hkv, d.n, attn, crit, budget, alpha, max_budget, idx, count, keys2, scratch, s);
+}
+
+// ---- budget allocation across the kv heads of a batch item (Algorithm 2, line 1) -------------------------
+// The P entries with the largest pooled score among all Hkv * n entries of a batch item are found with the
+// same selection kernels (one row of Hkv * n keys per batch item, attention only); a head's share is the
+// number of those entries it owns, located by binary search in the ascending index list.
+__global__ void allocate_fill_kernel(int32_t *pool_budget, int batch, int P)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < batch) pool_budget[i] = P;
+}
+
+__global__ void allocate_count_kernel(const int32_t *__restrict__ idx, int P, int Hkv, int n, int floor_each,
+                                      int32_t *__restrict__ budget_out)
+{
+    const int bi = blockIdx.x, g = threadIdx.x;
+    if (g >= Hkv) return;
+    const int32_t *row = idx + (size_t)bi * P;
+    auto lower_bound = [&](long long key) { // first position whose index is >= key
+        int lo = 0, hi = P;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if ((long long)row[mid] < key) lo = mid + 1; else hi = mid;
+        }
+        return lo;
+    };
+    const int owned = lower_bound((long long)(g + 1) * n) - lower_bound((long long)g * n);
+    budget_out[bi * Hkv + g] = min(n, floor_each + owned);
+}
+
+hipError_t launch_allocate(const Dims &d, const float *attn, int total, float floor_frac, int32_t *budget_out,
+                           uint32_t *keys2, uint32_t *scratch, int32_t *tmp, hipStream_t s)
+{
+    const int floor_each = (int)floor((double)floor_frac * (double)total / (double)d.Hkv);
+    const int P = (int)min((long long)total - (long long)d.Hkv * floor_each, (long long)d.Hkv * d.n);
+    int32_t *pool_budget = tmp;                 // [batch]
+    int32_t *pool_count = tmp + d.batch;        // [batch]
+    int32_t *pool_idx = tmp + 2 * d.batch;      // [batch][P]
+    if (P > 0) {
+        hipLaunchKernelGGL(allocate_fill_kernel, dim3((d.batch + 63) / 64), dim3(64), 0, s, pool_budget, d.batch, P);
+        hipError_t e = launch_select_rows(d.batch, d.Hkv * d.n, attn, attn, pool_budget, 1.0f, P, pool_idx, pool_count,
+                                          keys2, scratch, s);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(allocate_count_kernel, dim3(d.batch), dim3(((d.Hkv + 63) / 64) * 64), 0, s, pool_idx, P, d.Hkv, d.n,
+                       floor_each, budget_out);
     return hipGetLastError();
 }
 

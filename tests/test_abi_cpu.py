@@ -100,6 +100,13 @@ def test_null_pointers_workspace_and_ranges(lib):
     assert lib.criticalkv_select(ctypes.byref(d), p, p, p, 0.5, 1001, p, p, p, need, None) == P.CKV_E_INVALID_ARG
     assert lib.criticalkv_select(ctypes.byref(d), p, p, None, 0.5, 100, p, p, p, need, None) == P.CKV_E_INVALID_ARG
     assert lib.criticalkv_select(ctypes.byref(d), p, p, p, 0.5, 100, p, p, p, 16, None) == P.CKV_E_WORKSPACE
+    # allocate: total and floor ranges, workspace sized for the pooled list
+    assert lib.criticalkv_allocate(ctypes.byref(d), p, -1, 0.5, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_allocate(ctypes.byref(d), p, 100, 1.5, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_allocate(ctypes.byref(d), None, 100, 0.5, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_allocate(ctypes.byref(d), p, d.n_kv_heads * d.n_ctx + 1, 0.5, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_allocate(ctypes.byref(d), p, d.n_kv_heads * 1000, 0.0, p, p, 4096, None) == P.CKV_E_WORKSPACE
+    assert P.workspace_bytes(d, 1000) > need
     assert lib.criticalkv_compact(ctypes.byref(d), p, p, p, p, 0, p, p, None) == P.CKV_E_INVALID_ARG
     assert lib.criticalkv_compact(ctypes.byref(d), p, p, p, None, 10, p, p, None) == P.CKV_E_INVALID_ARG
 

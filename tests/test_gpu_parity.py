@@ -366,6 +366,79 @@ def test_budget_is_clamped_to_n_and_max_budget(P):
     assert np.all(idx[0, 1] == -1) and np.all(idx[0, 0] >= 0)
 
 
+# ------------------------------------------------------------------------------------------------ allocation
+def run_allocate(P, attn, total, floor_frac):
+    import torch
+    b, Hkv, n = attn.shape
+    desc = P.make_desc(batch=b, n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=128, d_model=128, n_ctx=n, window=1,
+                       pool_kernel=1, dtype=P.CKV_BF16)
+    ws = torch.empty(P.workspace_bytes(desc, -(-total // Hkv)), dtype=torch.uint8, device="cuda")
+    budget = torch.full((b, Hkv), -7, dtype=torch.int32, device="cuda")
+    P.criticalkv_allocate(desc, torch.from_numpy(np.ascontiguousarray(attn, dtype=np.float32)).cuda(), total, floor_frac,
+                          budget, workspace=ws)
+    torch.cuda.synchronize()
+    return budget.cpu().numpy()
+
+
+@pytest.mark.parametrize("n", [5, 1000, 4097, 40000])
+def test_allocate_exact_against_oracle(P, n):
+    """Same float32 scores on both sides: budgets are integers and must be identical."""
+    r = np.random.Generator(np.random.PCG64(77 + n))
+    Hkv = 8
+    # heads of different concentration, as in a real layer: some heads own most of the pooled top scores
+    attn = (r.random((2, Hkv, n)) ** r.integers(1, 9, (2, Hkv, 1))).astype(np.float32)
+    for total in (0, 1, Hkv, n, 3 * n + 1, Hkv * n):
+        for floor_frac in (0.0, 0.2, 0.5, 1.0):
+            got = run_allocate(P, attn, total, floor_frac)
+            ref = O.allocate(attn.astype(np.float64), total, np.float32(floor_frac))
+            assert np.array_equal(got, ref), (n, total, floor_frac, got, ref)
+            assert got.sum(axis=1).max() <= total
+
+
+def test_allocate_ties_and_pooled_scores(P):
+    r = np.random.Generator(np.random.PCG64(3))
+    n, Hkv = 6000, 4
+    few = r.integers(0, 5, (1, Hkv, n)).astype(np.float32)          # the threshold falls inside a large tie group
+    pooled = O.maxpool1d(r.random((1, Hkv, n)), 7).astype(np.float32)
+    same = np.broadcast_to(r.random((1, 1, n)).astype(np.float32), (1, Hkv, n)).copy()  # identical heads
+    for attn in (few, pooled, same):
+        for total in (7, 2 * n, 3 * n + 5):
+            for floor_frac in (0.0, 0.25):
+                got = run_allocate(P, attn, total, floor_frac)
+                ref = O.allocate(attn.astype(np.float64), total, np.float32(floor_frac))
+                assert np.array_equal(got, ref), (total, floor_frac, got, ref)
+
+
+def test_allocate_then_select_on_llama_shape(P):
+    """Scores from the GPU path, allocation on both sides from their own scores, then the two-stage selection
+    with the allocated budgets; the budgets may differ only through scores inside the 2e-3 band."""
+    import torch
+    cfg = reduced(CONFIGS["llama32k"], 4133)
+    t = make_layer(cfg)
+    total = cfg.n_kv_heads * cfg.budget
+    ref = O.score(t["q_win"], t["k"], t["v"], t["w_o"], pool_kernel=cfg.pool_kernel, eps=cfg.eps)
+    ff = np.float32(0.2)
+    ref_budget = O.allocate(ref.attn, total, ff)
+    res = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha)
+    got_on_gpu_scores = run_allocate(P, res.attn, total, ff)
+    assert np.array_equal(got_on_gpu_scores, O.allocate(res.attn.astype(np.float64), total, ff))
+    # slots may move between heads only through entries whose score lies in the 2e-3 band around the pooled threshold
+    floor_each = int(np.floor(float(ff) * total / cfg.n_kv_heads))
+    pool = total - cfg.n_kv_heads * floor_each
+    tau = np.sort(ref.attn.reshape(-1))[::-1][pool - 1]
+    band = int((np.abs(ref.attn - tau) <= 2e-3 * tau).sum())
+    moved = int(np.abs(got_on_gpu_scores - ref_budget).sum())
+    print(f"[allocate llama 4133] budgets {got_on_gpu_scores.tolist()} oracle {ref_budget.tolist()} moved slots {moved} "
+          f"(entries in the band: {band})")
+    assert got_on_gpu_scores.sum() == total and moved <= 2 * band
+    assert got_on_gpu_scores.min() >= floor_each and got_on_gpu_scores.std() > 0
+    res2 = run_gpu_pass(P, cfg, t, got_on_gpu_scores, cfg.alpha)
+    ref2 = O.full_pass(t["q_win"], t["k"], t["v"], t["w_o"], got_on_gpu_scores, cfg.alpha, pool_kernel=cfg.pool_kernel,
+                       eps=cfg.eps)
+    compare_selection(res2.idx, res2.count, ref2, got_on_gpu_scores, cfg.alpha)
+    assert np.array_equal(res2.count, got_on_gpu_scores)
+
+
 # ------------------------------------------------------------------------------------------------ full-size
 def _full_size_check(P, cfg, t, sweeps=None, layer_label=""):
     """Full BASELINE shape in the launch configuration the benchmark times (output-major W_O).

@@ -408,6 +408,34 @@ def test_select_batch_layout_and_compaction_bytes():
             assert not out[bi, g, B:].any()
 
 
+def test_budget_allocation_against_brute_force_and_closed_cases():
+    r = rng(60)
+    b, Hkv, n = 2, 4, 30
+    attn = r.random((b, Hkv, n)) * np.array([1.0, 2.0, 0.5, 1.5])[None, :, None]
+    for total, ff in [(40, 0.0), (40, 0.25), (41, 0.5), (120, 0.0), (0, 0.3), (17, 1.0)]:
+        got = O.allocate(attn, total, ff)
+        f = int(np.floor(ff * total / Hkv))
+        P = total - Hkv * f
+        for bi in range(b):
+            flat = attn[bi].reshape(-1)
+            order = np.lexsort((np.arange(flat.size), -flat))[:P]
+            ref = np.minimum(n, f + np.bincount(order // n, minlength=Hkv))
+            assert got[bi].tolist() == ref.tolist()
+            if ref.max() < n:
+                assert got[bi].sum() == total
+    # uniform split when the floor takes everything; all to the dominant head when its scores dominate
+    assert O.allocate(attn, 40, 1.0).tolist() == [[10] * 4] * 2
+    dom = attn.copy()
+    dom[:, 2] += 10.0
+    assert O.allocate(dom, 20, 0.0)[0].tolist() == [0, 0, 20, 0]
+    assert O.allocate(dom, 50, 0.0)[0, 2] == n            # capped at n, the rest spills to the other heads
+    # identical heads: ties go to the lower head first
+    same = np.tile(r.random((1, 1, n)), (1, Hkv, 1))
+    assert O.allocate(same, 6, 0.0)[0].tolist() == [2, 2, 1, 1]
+    with pytest.raises(RuntimeError):
+        O.allocate(attn, Hkv * n + 1, 0.0)
+
+
 def test_bad_arguments_are_rejected():
     a = np.ones(4)
     with pytest.raises(RuntimeError):
