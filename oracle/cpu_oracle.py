@@ -117,9 +117,10 @@ def group_keys(abar, N, n_kv_heads: int, eps: float = 1e-4, protect_last: int = 
     return attn, crit
 
 
-def select(attn, crit, budget, alpha: float, max_budget: Optional[int] = None):
+def select(attn, crit, budget, alpha: float, max_budget: Optional[int] = None, with_stage1: bool = False):
     """Two-stage selection per (batch, kv head).  Returns idx [b,Hkv,max_budget] (tail -1),
-    count [b,Hkv], tau [b,Hkv,2] (smallest key taken in stage 1 / stage 2)."""
+    count [b,Hkv], tau [b,Hkv,2] (smallest key taken in stage 1 / stage 2) and, with with_stage1,
+    the uint8 flags [b,Hkv,max_budget] of the entries taken in stage 1."""
     attn, ap = _f64(attn)
     crit, cp = _f64(crit)
     b, Hkv, n = attn.shape
@@ -131,12 +132,36 @@ def select(attn, crit, budget, alpha: float, max_budget: Optional[int] = None):
     idx = np.ascontiguousarray(idx)
     count = np.zeros((b, Hkv), dtype=np.int32)
     tau = np.empty((b, Hkv, 2), dtype=np.float64)
+    stage1 = np.zeros((b, Hkv, max_budget), dtype=np.uint8)
     rc = lib().ckvo_select(b * Hkv, n, ap, cp, bp, ctypes.c_double(float(alpha)), max_budget,
                            idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int)),
                            count.ctypes.data_as(ctypes.POINTER(ctypes.c_int)),
-                           tau.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+                           tau.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                           stage1.ctypes.data_as(ctypes.POINTER(ctypes.c_ubyte)))
     _check(rc, "select")
-    return idx, count, tau
+    return (idx, count, tau, stage1) if with_stage1 else (idx, count, tau)
+
+
+DIAG_FIELDS = ("sigma", "s", "C", "theta", "theta_hat", "theta_relax", "L", "M")
+
+
+def diagnostics(a_head, v, w_o, idx, count, stage1, norm: int = 1) -> np.ndarray:
+    """out[b,H,8] (DIAG_FIELDS) for the distribution a_head [b,H,n] and the selection (idx, count, stage1)."""
+    a_head, ap = _f64(a_head)
+    v, vp = _f32(v)
+    w_o, wp = _f32(w_o)
+    idx, ip = _i32(idx)
+    count, cp = _i32(count)
+    stage1 = np.ascontiguousarray(stage1, dtype=np.uint8)
+    b, H, n = a_head.shape
+    _, Hkv, _, dh = v.shape
+    assert w_o.shape[0] == H * dh and idx.shape == stage1.shape
+    out = np.empty((b, H, 8), dtype=np.float64)
+    rc = lib().ckvo_diagnostics(b, H, Hkv, dh, w_o.shape[1], n, norm, ap, vp, wp, idx.shape[-1], ip, cp,
+                                stage1.ctypes.data_as(ctypes.POINTER(ctypes.c_ubyte)),
+                                out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    _check(rc, "diagnostics")
+    return out
 
 
 def select_head(attn, crit, B: int, alpha: float):

@@ -281,10 +281,11 @@ int ckvo_select_head(int n, const double *attn, const double *crit, int B, doubl
 
 /*
  * Selection for all (batch, kv head) pairs.  attn, crit [b*Hkv, n]; budget [b*Hkv];
- * idx [b*Hkv, max_budget] (unused tail = -1); count [b*Hkv]; tau [b*Hkv, 2] or NULL.
+ * idx [b*Hkv, max_budget] (unused tail = -1); count [b*Hkv]; tau [b*Hkv, 2] or NULL;
+ * stage1 [b*Hkv, max_budget] or NULL: 1 where idx[j] was taken in stage 1.
  */
 int ckvo_select(int heads, int n, const double *attn, const double *crit, const int *budget,
-                double alpha, int max_budget, int *idx, int *count, double *tau)
+                double alpha, int max_budget, int *idx, int *count, double *tau, unsigned char *stage1)
 {
     int err = 0;
 #pragma omp parallel for schedule(dynamic)
@@ -297,7 +298,9 @@ int ckvo_select(int heads, int n, const double *attn, const double *crit, const 
             err = 1;
             continue;
         }
-        int rc = ckvo_select_head(n, attn + (size_t)hd * n, crit + (size_t)hd * n, B, alpha, out, NULL,
+        if (stage1) memset(stage1 + (size_t)hd * max_budget, 0, (size_t)max_budget);
+        int rc = ckvo_select_head(n, attn + (size_t)hd * n, crit + (size_t)hd * n, B, alpha, out,
+                                  stage1 ? stage1 + (size_t)hd * max_budget : NULL,
                                   tau ? tau + 2 * (size_t)hd : NULL);
         if (rc != CKVO_OK) {
 #pragma omp atomic write
@@ -337,6 +340,98 @@ int ckvo_allocate(int b, int Hkv, int n, const double *attn, int total, double f
     }
     free(p);
     return CKVO_OK;
+}
+
+/*
+ * Perturbation quantities of a given selection, per (batch item, query head)
+ * (Definition 3.1; Theorems 3.2, 3.3, 3.5, 3.6; Assumption 3.4).
+ *
+ * For query head h (kv head g = h / G) let A = a[bi,h,:] be the head's attention distribution over the n
+ * entries (here the window mean of the softmax rows, before pooling; it sums to 1), P_i = v[bi,g,i,:] W_O^h
+ * the projected value of entry i, N_i = ||P_i|| (L1, or L2 with norm == 2), S the selected set
+ * idx[bi,g,0..count) and S1 its stage-1 part.  Written out from the definitions, nothing shortened:
+ *   sigma  = sum_{S1} A_i                     s = sum_{S} A_i
+ *   C      = sum_i A_i N_i                    M = min_i N_i
+ *   theta  = C - (2 - 1/s) sum_{S} A_i N_i                                     (Theorem 3.3)
+ *   C'     = C - (2 - 1/sigma) sum_{S1} A_i N_i
+ *   theta_hat   = C' - (2 - 1/sigma) sum_{S \ S1} A_i N_i                      (Theorem 3.5)
+ *   theta_relax = C' - M (2 - 1/sigma) sum_{S \ S1} A_i                        (Theorem 3.6)
+ *   L      = || sum_i (A_i - A'_i) P_i ||,   A'_i = A_i / s on S, 0 elsewhere   (Definition 3.1, Theorem 3.2)
+ * Empty sets: with S empty the pruned output is zero, so L = ||sum_i A_i P_i|| and theta = C; with S1
+ * empty (sigma = 0) the two stage-2 bounds say nothing and are reported as +infinity.
+ * out[bi,h,:] = { sigma, s, C, theta, theta_hat, theta_relax, L, M }.
+ */
+int ckvo_diagnostics(int b, int H, int Hkv, int d_h, int d_model, int n, int norm, const double *a,
+                     const float *v, const float *w_o, int max_budget, const int *idx, const int *count,
+                     const unsigned char *stage1, double *out)
+{
+    if (b < 1 || H < 1 || Hkv < 1 || H % Hkv || d_h < 1 || d_model < 1 || n < 1 || max_budget < 0) return CKVO_BAD_ARG;
+    if (norm != 1 && norm != 2) return CKVO_BAD_ARG;
+    const int G = H / Hkv;
+    int err = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int bi = 0; bi < b; ++bi) {
+        for (int h = 0; h < H; ++h) {
+            const int g = h / G;
+            const size_t hd = (size_t)bi * Hkv + g;
+            const double *A = a + ((size_t)bi * H + h) * (size_t)n;
+            const int cnt = count[hd];
+            /* masks N' (stage 1) and N'' (stage 2) of the theorems */
+            unsigned char *in1 = (unsigned char *)calloc((size_t)n, 1), *in2 = (unsigned char *)calloc((size_t)n, 1);
+            double *p = (double *)malloc(sizeof(double) * (size_t)d_model);
+            double *o = (double *)calloc((size_t)d_model, sizeof(double));
+            double *o_hat = (double *)calloc((size_t)d_model, sizeof(double));
+            int bad = !in1 || !in2 || !p || !o || !o_hat || cnt < 0 || cnt > max_budget;
+            for (int j = 0; !bad && j < cnt; ++j) {
+                const int i = idx[hd * max_budget + j];
+                if (i < 0 || i >= n) { bad = 1; break; }
+                if (stage1[hd * max_budget + j]) in1[i] = 1; else in2[i] = 1;
+            }
+            if (bad) {
+#pragma omp atomic write
+                err = 1;
+            } else {
+                double sigma = 0.0, s2 = 0.0;
+                for (int i = 0; i < n; ++i) { if (in1[i]) sigma += A[i]; if (in2[i]) s2 += A[i]; }
+                const double s = sigma + s2;
+                double C = 0.0, D1 = 0.0, D2 = 0.0, M = INFINITY;
+                for (int i = 0; i < n; ++i) {
+                    const float *vv = v + (hd * (size_t)n + i) * d_h;
+                    for (int c = 0; c < d_model; ++c) p[c] = 0.0;
+                    for (int t = 0; t < d_h; ++t) {
+                        const double vt = (double)vv[t];
+                        const float *wrow = w_o + ((size_t)h * d_h + t) * (size_t)d_model;
+                        for (int c = 0; c < d_model; ++c) p[c] += vt * (double)wrow[c];
+                    }
+                    double N = 0.0;
+                    if (norm == 1) { for (int c = 0; c < d_model; ++c) N += fabs(p[c]); }
+                    else { for (int c = 0; c < d_model; ++c) N += p[c] * p[c]; N = sqrt(N); }
+                    C += A[i] * N;
+                    if (in1[i]) D1 += A[i] * N;
+                    if (in2[i]) D2 += A[i] * N;
+                    if (N < M) M = N;
+                    const double A_hat = (in1[i] || in2[i]) ? A[i] / s : 0.0;
+                    for (int c = 0; c < d_model; ++c) { o[c] += A[i] * p[c]; o_hat[c] += A_hat * p[c]; }
+                }
+                double L = 0.0;
+                if (norm == 1) { for (int c = 0; c < d_model; ++c) L += fabs(o[c] - o_hat[c]); }
+                else { for (int c = 0; c < d_model; ++c) L += (o[c] - o_hat[c]) * (o[c] - o_hat[c]); L = sqrt(L); }
+                double *r = out + ((size_t)bi * H + h) * 8;
+                r[0] = sigma; r[1] = s; r[2] = C; r[7] = M;
+                r[3] = s > 0.0 ? C - (2.0 - 1.0 / s) * (D1 + D2) : C;
+                if (sigma > 0.0) {
+                    const double C1 = C - (2.0 - 1.0 / sigma) * D1;
+                    r[4] = C1 - (2.0 - 1.0 / sigma) * D2;
+                    r[5] = C1 - M * (2.0 - 1.0 / sigma) * s2;
+                } else {
+                    r[4] = r[5] = INFINITY;
+                }
+                r[6] = L;
+            }
+            free(in1); free(in2); free(p); free(o); free(o_hat);
+        }
+    }
+    return err ? CKVO_BAD_ARG : CKVO_OK;
 }
 
 /*

@@ -436,6 +436,127 @@ def test_budget_allocation_against_brute_force_and_closed_cases():
         O.allocate(attn, Hkv * n + 1, 0.0)
 
 
+# ------------------------------------------------------------------------------------------------ diagnostics
+def _diag(A, v, w, keep1, keep2, norm=1):
+    """One head through the oracle's diagnostics: A [n], v [n,dh], w [dh,dm], index lists of the two stages."""
+    n = len(A)
+    sel = sorted(list(keep1) + list(keep2))
+    mb = max(1, len(sel))
+    idx = np.full((1, 1, mb), -1, dtype=np.int32)
+    idx[0, 0, :len(sel)] = sel
+    st1 = np.zeros((1, 1, mb), dtype=np.uint8)
+    st1[0, 0, :len(sel)] = [i in set(keep1) for i in sel]
+    out = O.diagnostics(np.asarray(A, dtype=np.float64)[None, None], np.asarray(v, dtype=np.float32)[None, None],
+                        np.asarray(w, dtype=np.float32), idx, np.array([[len(sel)]], dtype=np.int32), st1, norm)
+    return dict(zip(O.DIAG_FIELDS, out[0, 0]))
+
+
+def test_diagnostics_hand_worked_fixture():
+    rows = {}
+    for line in open(os.path.join(GOLDEN, "perturbation_hand_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, *vals = line.split()
+        rows[key] = [float(x) for x in vals]
+    A, N = np.array(rows["A"]), np.array(rows["N"])
+    k1, k2 = [int(x) for x in rows["stage1"]], [int(x) for x in rows["stage2"]]
+    layouts = {"orthogonal": (np.diag(N), np.eye(3)), "parallel": (N[:, None], np.ones((1, 1)))}
+    for name, (v, w) in layouts.items():
+        for norm in (1, 2):
+            d = _diag(A, v, w, k1, k2, norm)
+            for f in ("sigma", "s", "C", "M", "theta", "theta_hat", "theta_relax"):
+                np.testing.assert_allclose(d[f], rows[f][0], rtol=1e-12, err_msg=f"{name} {f}")
+            np.testing.assert_allclose(d["L"], rows[f"L{norm}_{name}"][0], rtol=1e-7, err_msg=f"{name} L{norm}")
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_diagnostics_L_is_the_masked_softmax_perturbation(seed):
+    """One window query: L equals ||o - o_hat||_1 with o_hat from the softmax over the kept logits only
+    (the additive -inf mask of section 3.1), for every subset; theta equals sum_i |A_i - A'_i| N_i, the
+    quantity the proof of Theorem 3.3 bounds L with."""
+    n, b = 8, 3
+    q, k, v, w = _tiny_head(300 + seed, n=n)
+    A = O.window_attention(q, k)[0, 0]
+    Vn = O.projected_value_norm(v, w, 1)[0, 0]
+    P = v[0, 0].astype(np.float64) @ w.astype(np.float64)
+    logits = q[0, 0, 0].astype(np.float64) @ k[0, 0].astype(np.float64).T / np.sqrt(q.shape[-1])
+    o_full = scipy.special.softmax(logits) @ P
+    for keep in itertools.combinations(range(n), b):
+        masked = scipy.special.softmax(np.where(np.isin(np.arange(n), keep), logits, -np.inf))
+        d = _diag(A, v[0, 0], w, keep[:1], keep[1:])
+        np.testing.assert_allclose(d["L"], np.abs(o_full - masked @ P).sum(), rtol=1e-9, atol=1e-13)
+        np.testing.assert_allclose(d["theta"], (np.abs(A - masked) * Vn).sum(), rtol=1e-9, atol=1e-13)
+        np.testing.assert_allclose(d["sigma"], A[keep[0]], rtol=1e-12)
+        np.testing.assert_allclose(d["s"], A[list(keep)].sum(), rtol=1e-12)
+        np.testing.assert_allclose(d["C"], A @ Vn, rtol=1e-12)
+        assert d["M"] == Vn.min()
+        assert d["L"] <= d["theta"] * (1 + 1e-12) <= d["theta_hat"] * (1 + 1e-11)
+        if d["sigma"] >= 0.5:
+            assert d["theta_hat"] <= d["theta_relax"] * (1 + 1e-12)
+        # L2: the Euclidean norm of the same difference vector
+        d2 = _diag(A, v[0, 0], w, keep[:1], keep[1:], norm=2)
+        np.testing.assert_allclose(d2["L"], np.sqrt(((o_full - masked @ P) ** 2).sum()), rtol=1e-9, atol=1e-13)
+
+
+def test_diagnostics_closed_cases():
+    r = rng(17)
+    n, dh, dm = 12, 4, 5
+    A = r.random(n)
+    A /= A.sum()
+    v = r.standard_normal((n, dh))
+    w = r.standard_normal((dh, dm))
+    everything = _diag(A, v, w, range(0, 5), range(5, n))
+    assert abs(everything["L"]) < 1e-12 and abs(everything["theta"]) < 1e-12 and abs(everything["s"] - 1) < 1e-12
+    # stage 2 empty: s = sigma, so theta_hat collapses onto theta (and so does the relaxed bound)
+    only1 = _diag(A, v, w, [1, 4, 7], [])
+    np.testing.assert_allclose(only1["theta_hat"], only1["theta"], rtol=1e-12)
+    np.testing.assert_allclose(only1["theta_relax"], only1["theta"], rtol=1e-12)
+    # nothing kept: the pruned output is zero
+    P = np.float32(v).astype(np.float64) @ np.float32(w).astype(np.float64)
+    none = _diag(A, v, w, [], [])
+    np.testing.assert_allclose(none["L"], np.abs(A @ P).sum(), rtol=1e-12)
+    np.testing.assert_allclose(none["theta"], none["C"], rtol=1e-15)
+    assert none["sigma"] == 0 and np.isinf(none["theta_hat"]) and np.isinf(none["theta_relax"])
+    # stage 1 empty only
+    no1 = _diag(A, v, w, [], [2, 3])
+    assert np.isinf(no1["theta_hat"]) and np.isfinite(no1["theta"]) and no1["L"] <= no1["theta"]
+    # identical projected values: any selection reproduces the output exactly
+    same = _diag(A, np.tile(v[:1], (n, 1)), w, [0], [5, 6])
+    assert same["L"] < 1e-12 * same["C"]
+    # equal magnitudes N_i = 1 (signed unit vectors through the identity): the relaxed bound is not relaxed
+    signs = np.eye(dh)[r.integers(0, dh, n)] * r.choice([-1.0, 1.0], (n, 1))
+    eq = _diag(A, signs, np.eye(dh), [int(np.argmax(A))], [2, 3] if int(np.argmax(A)) not in (2, 3) else [4, 5])
+    np.testing.assert_allclose(eq["theta_relax"], eq["theta_hat"], rtol=1e-12)
+    assert eq["M"] == 1.0
+
+
+def test_diagnostics_head_layout_and_chain_on_tiny_config():
+    """GQA layout: query head h reads kv head h / G, its own W_O slice and its own A; and on the synthetic
+    workload the chain L <= theta <= theta_hat (<= theta_relax when sigma >= 0.5) holds for every head."""
+    cfg = CONFIGS["tiny"]
+    t = make_layer(cfg)
+    r = O.score(t["q_win"], t["k"], t["v"], t["w_o"], pool_kernel=cfg.pool_kernel, eps=cfg.eps)
+    idx, count, _, st1 = O.select(r.attn, r.crit, cfg.budget, cfg.alpha, with_stage1=True)
+    out = O.diagnostics(r.a_head, t["v"], t["w_o"], idx, count, st1)
+    b, H, Hkv, dh = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    G = H // Hkv
+    assert out.shape == (b, H, 8)
+    for bi in range(b):
+        for h in range(H):
+            g = h // G
+            c = int(count[bi, g])
+            sel = idx[bi, g, :c]
+            one = _diag(r.a_head[bi, h], t["v"][bi, g], t["w_o"][h * dh:(h + 1) * dh], sel[st1[bi, g, :c] > 0],
+                        sel[st1[bi, g, :c] == 0])
+            np.testing.assert_allclose(out[bi, h], [one[f] for f in O.DIAG_FIELDS], rtol=1e-12)
+            d = dict(zip(O.DIAG_FIELDS, out[bi, h]))
+            np.testing.assert_allclose(d["C"], r.a_head[bi, h] @ r.vnorm[bi, h], rtol=1e-12)
+            assert d["L"] <= d["theta"] * (1 + 1e-12) <= d["theta_hat"] * (1 + 1e-11)
+            if d["sigma"] >= 0.5:
+                assert d["theta_hat"] <= d["theta_relax"] * (1 + 1e-12)
+    assert (st1.sum(axis=-1) == int(np.floor(cfg.alpha * cfg.budget))).all()
+
+
 def test_bad_arguments_are_rejected():
     a = np.ones(4)
     with pytest.raises(RuntimeError):
