@@ -105,7 +105,7 @@ typedef struct ckv_layer_desc {
 
 /*
  * Bytes of workspace that criticalkv_score, criticalkv_select and criticalkv_allocate need for this
- * layer (the largest of them; compact needs none).  max_budget only sizes criticalkv_allocate's list.  Returns 0 if the descriptor is invalid.
+ * layer, criticalkv_diagnostics included (the largest of them; compact needs none).  max_budget only sizes criticalkv_allocate's list.  Returns 0 if the descriptor is invalid.
  * Host-only computation.
  */
 CKV_API size_t criticalkv_workspace_bytes(const ckv_layer_desc *desc, int32_t max_budget);
@@ -203,6 +203,48 @@ CKV_API int criticalkv_select(const ckv_layer_desc *desc, const float *attn, con
 CKV_API int criticalkv_allocate(const ckv_layer_desc *desc, const float *attn, int32_t total_budget,
                                 float floor_frac, int32_t *budget, void *workspace, size_t workspace_bytes,
                                 void *hip_stream);
+
+/*
+ * Perturbation quantities of a finished selection, per (batch item, query head)
+ * (Definition 3.1; Theorems 3.2, 3.3, 3.5, 3.6; Assumption 3.4): what the paper's analysis plots.
+ *
+ * For query head h (kv head g = h / G): A = the head's window-mean attention over the n entries, before
+ * pooling (it sums to 1; the theorems are stated for one query's distribution, the window mean takes its
+ * place); P_i = v[bi,g,i,:] W^O_h; N_i = ||P_i|| in the descriptor's norm; S = idx[bi,g,0..count) and
+ * S1 the part of it taken in stage 1.
+ *   out[bi,h,CKV_DIAG_SIGMA]       sigma = sum_{S1} A_i                     (Assumption 3.4 asks > 0.5)
+ *   out[bi,h,CKV_DIAG_S]           s     = sum_{S} A_i
+ *   out[bi,h,CKV_DIAG_C]           C     = sum_i A_i N_i
+ *   out[bi,h,CKV_DIAG_THETA]       C - (2 - 1/s) sum_{S} A_i N_i                              (Thm 3.3)
+ *   out[bi,h,CKV_DIAG_THETA_HAT]   C' - (2 - 1/sigma) sum_{S\S1} A_i N_i,
+ *                                  C' = C - (2 - 1/sigma) sum_{S1} A_i N_i                    (Thm 3.5)
+ *   out[bi,h,CKV_DIAG_THETA_RELAX] C' - M (2 - 1/sigma) sum_{S\S1} A_i                        (Thm 3.6)
+ *   out[bi,h,CKV_DIAG_L]           || sum_i (A_i - A'_i) P_i ||, A' = A on S renormalised     (Def. 3.1, Thm 3.2)
+ *   out[bi,h,CKV_DIAG_M]           M = min_i N_i
+ * S empty: L = ||sum_i A_i P_i|| and theta = C.  S1 empty: theta_hat = theta_relax = +inf.
+ *
+ * STATE: reads what criticalkv_score and then criticalkv_select left in `workspace` for this descriptor
+ * (the unpooled scores, the magnitudes, the stage-1 marks).  Call it after those two, with the same
+ * descriptor and workspace and no other call on that workspace in between; anything else gives
+ * undefined values (never a fault).  The descriptor must not carry CKV_ATTN_ONLY or CKV_WO_IS_GRAM.
+ *
+ * in : v, idx, count, max_budget as given to / returned by the two calls; w_o the projection itself in
+ *      the layout the descriptor names; vnorm_opt the pointer criticalkv_score was given (NULL if none)
+ * out: out [batch, H, CKV_N_DIAG] float32, DEVICE
+ */
+#define CKV_DIAG_SIGMA 0
+#define CKV_DIAG_S 1
+#define CKV_DIAG_C 2
+#define CKV_DIAG_THETA 3
+#define CKV_DIAG_THETA_HAT 4
+#define CKV_DIAG_THETA_RELAX 5
+#define CKV_DIAG_L 6
+#define CKV_DIAG_M 7
+#define CKV_N_DIAG 8
+CKV_API int criticalkv_diagnostics(const ckv_layer_desc *desc, const void *v, const void *w_o,
+                                   const float *vnorm_opt, const int32_t *idx, const int32_t *count,
+                                   int32_t max_budget, float *out, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream);
 
 /*
  * Compacted cache (Algorithm 1 line 10):  k_out[bi,g,j,:] = k[bi,g,idx[bi,g,j],:] for j < count[bi,g],

@@ -23,7 +23,7 @@ CKV_OK, CKV_E_INVALID_ARG, CKV_E_UNSUPPORTED, CKV_E_WORKSPACE, CKV_E_HIP = 0, -1
 
 EXPORTS = ("criticalkv_workspace_bytes", "criticalkv_score", "criticalkv_score_profiled", "criticalkv_select",
            "criticalkv_compact", "criticalkv_strerror", "criticalkv_gram_bytes", "criticalkv_prepare_gram",
-           "criticalkv_allocate")
+           "criticalkv_allocate", "criticalkv_diagnostics")
 STAGES = ("wo_layout", "attn_stats", "attn_colsum", "vproj", "combine")
 
 
@@ -92,6 +92,8 @@ def load() -> ctypes.CDLL:
         lib.criticalkv_select.argtypes = [dp, vp, vp, vp, f32, i32, vp, vp, vp, ctypes.c_size_t, vp]
         lib.criticalkv_allocate.restype = ctypes.c_int
         lib.criticalkv_allocate.argtypes = [dp, vp, i32, f32, vp, vp, ctypes.c_size_t, vp]
+        lib.criticalkv_diagnostics.restype = ctypes.c_int
+        lib.criticalkv_diagnostics.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, vp, ctypes.c_size_t, vp]
         lib.criticalkv_compact.restype = ctypes.c_int
         lib.criticalkv_compact.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp]
         lib.criticalkv_strerror.restype = ctypes.c_char_p
@@ -174,7 +176,19 @@ def criticalkv_allocate(desc: LayerDesc, attn, total_budget: int, floor_frac: fl
     rc = load().criticalkv_allocate(ctypes.byref(desc), _ptr(attn), int(total_budget), float(floor_frac), _ptr(budget),
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != CKV_OK:
-        raise CriticalKVError(rc, "criticalkv_allocate")
+        raise CriticalKVError(rc, "criticalkv_allocate", "criticalkv_diagnostics")
+
+
+DIAG_FIELDS = ("sigma", "s", "C", "theta", "theta_hat", "theta_relax", "L", "M")
+
+
+def criticalkv_diagnostics(desc: LayerDesc, v, w_o, vnorm_opt, idx, count, max_budget: int, out, *, workspace,
+                           stream=None) -> None:
+    rc = load().criticalkv_diagnostics(ctypes.byref(desc), _ptr(v), _ptr(w_o), _ptr(vnorm_opt), _ptr(idx), _ptr(count),
+                                       int(max_budget), _ptr(out), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != CKV_OK:
+        raise CriticalKVError(rc, "criticalkv_diagnostics")
 
 
 def criticalkv_compact(desc: LayerDesc, k, v, idx, count, max_budget: int, k_out, v_out, *, stream=None) -> None:

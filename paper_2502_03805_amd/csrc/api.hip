@@ -74,6 +74,7 @@ Workspace carve_workspace(const Dims &d, int dtype, bool need_wt, int max_budget
     w.l2_scratch = off; if (d.norm == CKV_NORM_L2 && d.dh == 128) off = align256(off + vproj_l2_workspace_bytes(d));
     w.sel_keys = off; off = align256(off + (size_t)d.batch * d.Hkv * d.n * 4);
     w.sel_scratch = off; off = align256(off + select_workspace_words(d.batch * d.Hkv, d.n) * 4);
+    w.diag_part = off; off = align256(off + diagnostics_workspace_floats(d) * 4);
     // last, so that the offsets above do not depend on max_budget
     w.alloc_tmp = off; off = align256(off + ((size_t)2 * d.batch + (size_t)d.batch * d.Hkv * (max_budget > 0 ? max_budget : 0)) * 4);
     w.total = off;
@@ -263,6 +264,27 @@ int criticalkv_allocate(const ckv_layer_desc *desc, const float *attn, int32_t t
     uint32_t *scratch = (uint32_t *)((char *)workspace + ws.sel_scratch);
     int32_t *tmp = (int32_t *)((char *)workspace + ws.alloc_tmp);
     hipError_t e = launch_allocate(d, attn, total_budget, floor_frac, budget, keys2, scratch, tmp, (hipStream_t)hip_stream);
+    return e == hipSuccess ? CKV_OK : CKV_E_HIP;
+}
+
+int criticalkv_diagnostics(const ckv_layer_desc *desc, const void *v, const void *w_o, const float *vnorm_opt,
+                           const int32_t *idx, const int32_t *count, int32_t max_budget, float *out, void *workspace,
+                           size_t workspace_bytes, void *hip_stream)
+{
+    Dims d;
+    int rc = resolve(desc, &d);
+    if (rc != CKV_OK) return rc;
+    if (!v || !w_o || !idx || !count || !out) return CKV_E_INVALID_ARG;
+    if (desc->flags & (CKV_ATTN_ONLY | CKV_WO_IS_GRAM)) return CKV_E_INVALID_ARG; // needs the magnitudes and W_O itself
+    if (max_budget < 1 || max_budget > d.n) return CKV_E_INVALID_ARG;
+    const Workspace ws = carve_workspace(d, desc->dtype, false, 0); // the layout criticalkv_select used
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
+    char *base = (char *)workspace;
+    const float *vnorm = vnorm_opt ? vnorm_opt : (const float *)(base + ws.vnorm);
+    hipError_t e = launch_diagnostics(d, desc->dtype, (desc->flags & CKV_WO_OUT_IN) ? 1 : 0, v, w_o,
+                                      (const float *)(base + ws.a_raw), vnorm, (const uint32_t *)(base + ws.sel_keys),
+                                      idx, count, max_budget, (float *)(base + ws.diag_part), out,
+                                      (hipStream_t)hip_stream);
     return e == hipSuccess ? CKV_OK : CKV_E_HIP;
 }
 

@@ -36,6 +36,7 @@ struct Workspace {
     size_t w_t;        // [d_model, H*dh] copy of W_O in output-major layout (when given canonical)
     size_t sel_keys;   // [batch*Hkv, n] u32: stage-2 keys with stage-1 entries marked
     size_t l2_scratch; // Gram partial sums and the split bf16 Gram matrices (L2 norm only)
+    size_t diag_part;  // per-chunk partial sums of the perturbation diagnostics
     size_t alloc_tmp;  // budget allocation: pool budgets, counts and the pooled index list
     size_t sel_scratch; // digit histograms, per-head state, per-slice counts of the selection kernels
     size_t total;
@@ -88,6 +89,11 @@ hipError_t launch_select(const Dims &d, const float *attn, const float *crit, co
 // per-head budgets from a per-batch-item total; tmp holds 2 * batch + batch * total int32
 hipError_t launch_allocate(const Dims &d, const float *attn, int total, float floor_frac, int32_t *budget_out,
                            uint32_t *keys2, uint32_t *scratch, int32_t *tmp, hipStream_t s);
+// perturbation quantities of a finished selection; part holds diagnostics_workspace_floats(d) floats
+size_t diagnostics_workspace_floats(const Dims &d);
+hipError_t launch_diagnostics(const Dims &d, int dtype, int out_in, const void *v, const void *w_o, const float *a_raw,
+                              const float *vnorm, const uint32_t *keys2, const int32_t *idx, const int32_t *count,
+                              int max_budget, float *part, float *out, hipStream_t s);
 hipError_t launch_compact(const Dims &d, int dtype, const void *k, const void *v, const int32_t *idx,
                           const int32_t *count, int max_budget, void *k_out, void *v_out, hipStream_t s);
 

@@ -1,0 +1,282 @@
+// Perturbation quantities of a finished selection, per (batch item, query head)
+// (Definition 3.1; Theorems 3.2, 3.3, 3.5, 3.6; Assumption 3.4).
+//
+// With A the head's window-mean attention (unpooled, sums to 1), N_i the projected-value norm, S the
+// selected set and S1 its stage-1 part:
+//   sigma = sum_{S1} A_i, s = sum_S A_i, C = sum_i A_i N_i, M = min_i N_i,
+//   theta (Thm 3.3), theta_hat (Thm 3.5), theta_relax (Thm 3.6) from those sums, and
+//   L = || sum_i (A_i - A'_i) (V W_O)_i || with A' = A restricted to S and renormalised (Thm 3.2).
+// The projection is linear, so  sum_i (A_i - A'_i) v_i W_O = (u_all - u_S / s) W_O  with the d_h-vectors
+// u_all = sum_i A_i v_i and u_S = sum_{S} A_i v_i: V is read once per kv head (plus the selected rows once
+// more) and W_O once per query head, instead of materialising V W_O.
+//
+//   sweep     one workgroup per (1024-token chunk, kv head): partial u_all, C, M for the group's query heads
+//   selected  one workgroup per (1024-entry chunk of the index list, kv head): partial u_S and the four
+//             sums over S1 / S2; stage-1 membership is read from the selection's stage-2 key array
+//   finish    one workgroup per query head: chunk partials summed in double in a fixed order, the
+//             d_h x d matrix-vector product, the norm of the result and the closed forms
+#include "common.hpp"
+
+namespace ckv {
+
+constexpr int DG_THREADS = 256;
+constexpr int DG_CHUNK = 1024;
+constexpr int DG_GMAX = 8; // query heads of a group handled by one workgroup (more: blockIdx.z)
+constexpr uint32_t DG_TAKEN = 0xFFFFFFFFu; // the selection's mark for stage-1 entries in its stage-2 keys
+
+struct DiagArgs {
+    const float *a_raw;   // [batch, H, n]
+    const float *vnorm;   // [batch, H, n]
+    const uint32_t *keys2; // [batch*Hkv, n]
+    const int32_t *idx;   // [batch*Hkv, max_budget]
+    const int32_t *count; // [batch*Hkv]
+    const void *v;
+    float *part_all;      // [batch*H][n_chunks][dh + 2]: u_all, C, M
+    float *part_sel;      // [batch*H][n_chunks][dh + 4]: u_S, sigma, s2, D1, D2
+    int H, Hkv, G, dh, n, max_budget, n_chunks;
+    float a_scale;        // 1, or 1/W when the stored score is the window sum
+    int64_t vs0, vs1, vs2;
+};
+
+__device__ __forceinline__ double block_sum_f64(double x, double *sh)
+{
+    __syncthreads();
+    sh[threadIdx.x] = x;
+    __syncthreads();
+    for (int o = DG_THREADS / 2; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+        __syncthreads();
+    }
+    return sh[0];
+}
+
+__device__ __forceinline__ float block_sum_f32(float x, float *sh)
+{
+    __syncthreads();
+    sh[threadIdx.x] = x;
+    __syncthreads();
+    for (int o = DG_THREADS / 2; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+        __syncthreads();
+    }
+    return sh[0];
+}
+
+__device__ __forceinline__ float block_min_f32(float x, float *sh)
+{
+    __syncthreads();
+    sh[threadIdx.x] = x;
+    __syncthreads();
+    for (int o = DG_THREADS / 2; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) sh[threadIdx.x] = fminf(sh[threadIdx.x], sh[threadIdx.x + o]);
+        __syncthreads();
+    }
+    return sh[0];
+}
+
+// SELECTED = false: tokens [chunk * 1024, ...) of the head.  SELECTED = true: entries j of the index list.
+template <typename T, bool SELECTED>
+__global__ __launch_bounds__(DG_THREADS) void diag_partial_kernel(DiagArgs A)
+{
+    __shared__ float a_s[DG_GMAX][DG_CHUNK];   // A of the chunk's tokens, per query head of the group
+    __shared__ int tok_s[DG_CHUNK];            // SELECTED: token index (-1 = skip); stage-1 flag in st1_s
+    __shared__ unsigned char st1_s[DG_CHUNK];
+    __shared__ float red_s[DG_THREADS];
+    __shared__ float u_s[DG_THREADS];
+
+    const int chunk = blockIdx.x, head = blockIdx.y; // head = bi * Hkv + g
+    const int bi = head / A.Hkv, g = head % A.Hkv;
+    const int hh0 = blockIdx.z * DG_GMAX, gc = min(DG_GMAX, A.G - hh0);
+    const int h0 = g * A.G + hh0;                                    // first query head handled here
+    const int limit = SELECTED ? min(max(A.count[head], 0), A.max_budget) : A.n;
+    const int j0 = chunk * DG_CHUNK;
+    const int len = min(DG_CHUNK, limit - j0);
+    const bool empty = len <= 0; // uniform over the workgroup; partials of an empty chunk are written as zeros
+
+    for (int jj = threadIdx.x; jj < DG_CHUNK; jj += DG_THREADS) {
+        int i = -1;
+        unsigned char st1 = 0;
+        if (jj < len) {
+            if (SELECTED) {
+                i = A.idx[(size_t)head * A.max_budget + j0 + jj];
+                if (i < 0 || i >= A.n) i = -1;
+                else st1 = A.keys2[(size_t)head * A.n + i] == DG_TAKEN;
+            } else {
+                i = j0 + jj;
+            }
+        }
+        tok_s[jj] = i;
+        st1_s[jj] = st1;
+        for (int hh = 0; hh < gc; ++hh)
+            a_s[hh][jj] = i >= 0 ? A.a_raw[((size_t)bi * A.H + h0 + hh) * A.n + i] * A.a_scale : 0.0f;
+    }
+    __syncthreads();
+
+    // scalar sums: thread-strided over the chunk, then reduced over the workgroup
+    for (int hh = 0; hh < gc; ++hh) {
+        const float *nrm = A.vnorm + ((size_t)bi * A.H + h0 + hh) * A.n;
+        float c0 = 0.0f, c1 = 0.0f, c2 = 0.0f, c3 = 0.0f, mn = INFINITY;
+        for (int jj = threadIdx.x; jj < DG_CHUNK; jj += DG_THREADS) {
+            const int i = tok_s[jj];
+            if (i < 0) continue;
+            const float a = a_s[hh][jj], N = nrm[i];
+            if (SELECTED) {
+                if (st1_s[jj]) { c0 += a; c2 += a * N; } else { c1 += a; c3 += a * N; }
+            } else {
+                c0 += a * N;
+                mn = fminf(mn, N);
+            }
+        }
+        float *dst = SELECTED ? A.part_sel + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 4) + A.dh
+                              : A.part_all + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 2) + A.dh;
+        c0 = block_sum_f32(c0, red_s);
+        if (SELECTED) {
+            c1 = block_sum_f32(c1, red_s);
+            c2 = block_sum_f32(c2, red_s);
+            c3 = block_sum_f32(c3, red_s);
+            if (threadIdx.x == 0) { dst[0] = c0; dst[1] = c1; dst[2] = c2; dst[3] = c3; }
+        } else {
+            mn = block_min_f32(mn, red_s);
+            if (threadIdx.x == 0) { dst[0] = c0; dst[1] = mn; }
+        }
+    }
+
+    // weighted value sums: thread = (token lane, column)
+    const int col = threadIdx.x % A.dh, lane = threadIdx.x / A.dh, lanes = DG_THREADS / A.dh;
+    float acc[DG_GMAX];
+#pragma unroll
+    for (int hh = 0; hh < DG_GMAX; ++hh) acc[hh] = 0.0f;
+    if (!empty) {
+        const T *vb = reinterpret_cast<const T *>(A.v) + bi * A.vs0 + g * A.vs1;
+        for (int jj = lane; jj < len; jj += lanes) {
+            const int i = tok_s[jj];
+            if (i < 0) continue;
+            const float x = to_f32(vb[(int64_t)i * A.vs2 + col]);
+#pragma unroll
+            for (int hh = 0; hh < DG_GMAX; ++hh)
+                if (hh < gc) acc[hh] += a_s[hh][jj] * x;
+        }
+    }
+    for (int hh = 0; hh < gc; ++hh) {
+        float x = 0.0f;
+#pragma unroll
+        for (int q = 0; q < DG_GMAX; ++q)
+            if (q == hh) x = acc[q];
+        __syncthreads();
+        u_s[threadIdx.x] = x;
+        __syncthreads();
+        if ((int)threadIdx.x < A.dh) {
+            float sum = 0.0f;
+            for (int l = 0; l < lanes; ++l) sum += u_s[l * A.dh + threadIdx.x];
+            float *dst = SELECTED ? A.part_sel + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 4)
+                                  : A.part_all + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 2);
+            dst[threadIdx.x] = sum;
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(DG_THREADS) void diag_finish_kernel(DiagArgs A, const void *w_o, int dm, int out_in,
+                                                                 int norm, float *out)
+{
+    __shared__ double red_s[DG_THREADS];
+    __shared__ double diff_s[128];
+    __shared__ double scal_s[8];
+    const int bh = blockIdx.x; // bi * H + h
+    const int bi = bh / A.H, h = bh % A.H, g = h / A.G;
+    const int head = bi * A.Hkv + g;
+    const int cnt = min(max(A.count[head], 0), A.max_budget);
+    const int sel_chunks = (cnt + DG_CHUNK - 1) / DG_CHUNK;
+    const float *pa = A.part_all + (size_t)bh * A.n_chunks * (A.dh + 2);
+    const float *ps = A.part_sel + (size_t)bh * A.n_chunks * (A.dh + 4);
+
+    if (threadIdx.x < 6) {
+        // 0: C  1: M  2: sigma  3: s2  4: D1  5: D2 -- each summed over its chunks in ascending order
+        const int q = threadIdx.x;
+        double acc = q == 1 ? (double)INFINITY : 0.0;
+        if (q < 2) {
+            for (int c = 0; c < A.n_chunks; ++c) {
+                const double x = (double)pa[(size_t)c * (A.dh + 2) + A.dh + q];
+                acc = q == 1 ? fmin(acc, x) : acc + x;
+            }
+        } else {
+            for (int c = 0; c < sel_chunks; ++c) acc += (double)ps[(size_t)c * (A.dh + 4) + A.dh + (q - 2)];
+        }
+        scal_s[q] = acc;
+    }
+    __syncthreads();
+    const double C = scal_s[0], M = scal_s[1], sigma = scal_s[2], s2 = scal_s[3], D1 = scal_s[4], D2 = scal_s[5];
+    const double s = sigma + s2;
+    if ((int)threadIdx.x < A.dh) {
+        double ua = 0.0, us = 0.0;
+        for (int c = 0; c < A.n_chunks; ++c) ua += (double)pa[(size_t)c * (A.dh + 2) + threadIdx.x];
+        for (int c = 0; c < sel_chunks; ++c) us += (double)ps[(size_t)c * (A.dh + 4) + threadIdx.x];
+        diff_s[threadIdx.x] = s > 0.0 ? ua - us / s : ua;
+    }
+    __syncthreads();
+    // y = diff W_O^h, then its norm
+    const T *w = reinterpret_cast<const T *>(w_o);
+    double part = 0.0;
+    for (int m = threadIdx.x; m < dm; m += DG_THREADS) {
+        double y = 0.0;
+        if (out_in) {
+            const T *row = w + (size_t)m * ((size_t)A.H * A.dh) + (size_t)h * A.dh;
+            for (int c = 0; c < A.dh; ++c) y += diff_s[c] * (double)to_f32(row[c]);
+        } else {
+            const T *colp = w + (size_t)h * A.dh * dm + m;
+            for (int c = 0; c < A.dh; ++c) y += diff_s[c] * (double)to_f32(colp[(size_t)c * dm]);
+        }
+        part += norm == CKV_NORM_L2 ? y * y : fabs(y);
+    }
+    double L = block_sum_f64(part, red_s);
+    if (norm == CKV_NORM_L2) L = sqrt(L);
+    if (threadIdx.x == 0) {
+        float *r = out + (size_t)bh * 8;
+        const double inf = (double)INFINITY;
+        r[0] = (float)sigma; r[1] = (float)s; r[2] = (float)C; r[7] = (float)M;
+        r[3] = (float)(s > 0.0 ? C - (2.0 - 1.0 / s) * (D1 + D2) : C);
+        if (sigma > 0.0) {
+            const double C1 = C - (2.0 - 1.0 / sigma) * D1;
+            r[4] = (float)(C1 - (2.0 - 1.0 / sigma) * D2);
+            r[5] = (float)(C1 - M * (2.0 - 1.0 / sigma) * s2);
+        } else {
+            r[4] = (float)inf; r[5] = (float)inf;
+        }
+        r[6] = (float)L;
+    }
+}
+
+size_t diagnostics_workspace_floats(const Dims &d)
+{
+    const size_t n_chunks = (size_t)(d.n + DG_CHUNK - 1) / DG_CHUNK;
+    return (size_t)d.batch * d.H * n_chunks * (2 * (size_t)d.dh + 6);
+}
+
+hipError_t launch_diagnostics(const Dims &d, int dtype, int out_in, const void *v, const void *w_o, const float *a_raw,
+                              const float *vnorm, const uint32_t *keys2, const int32_t *idx, const int32_t *count,
+                              int max_budget, float *part, float *out, hipStream_t s)
+{
+    DiagArgs A;
+    A.a_raw = a_raw; A.vnorm = vnorm; A.keys2 = keys2; A.idx = idx; A.count = count; A.v = v;
+    A.H = d.H; A.Hkv = d.Hkv; A.G = d.G; A.dh = d.dh; A.n = d.n; A.max_budget = max_budget;
+    A.n_chunks = (d.n + DG_CHUNK - 1) / DG_CHUNK;
+    A.part_all = part;
+    A.part_sel = part + (size_t)d.batch * d.H * A.n_chunks * (d.dh + 2);
+    A.a_scale = d.window_sum ? 1.0f / (float)d.W : 1.0f;
+    A.vs0 = d.vs[0]; A.vs1 = d.vs[1]; A.vs2 = d.vs[2];
+    const int gz = (d.G + DG_GMAX - 1) / DG_GMAX;
+    const int sel_chunks = (max_budget + DG_CHUNK - 1) / DG_CHUNK;
+    dim3 block(DG_THREADS);
+    if (dtype == CKV_F32) {
+        hipLaunchKernelGGL((diag_partial_kernel<float, false>), dim3(A.n_chunks, d.batch * d.Hkv, gz), block, 0, s, A);
+        hipLaunchKernelGGL((diag_partial_kernel<float, true>), dim3(sel_chunks, d.batch * d.Hkv, gz), block, 0, s, A);
+        hipLaunchKernelGGL(diag_finish_kernel<float>, dim3(d.batch * d.H), block, 0, s, A, w_o, d.dm, out_in, d.norm, out);
+    } else {
+        hipLaunchKernelGGL((diag_partial_kernel<bf16_t, false>), dim3(A.n_chunks, d.batch * d.Hkv, gz), block, 0, s, A);
+        hipLaunchKernelGGL((diag_partial_kernel<bf16_t, true>), dim3(sel_chunks, d.batch * d.Hkv, gz), block, 0, s, A);
+        hipLaunchKernelGGL(diag_finish_kernel<bf16_t>, dim3(d.batch * d.H), block, 0, s, A, w_o, d.dm, out_in, d.norm, out);
+    }
+    return hipGetLastError();
+}
+
+} // namespace ckv

@@ -107,6 +107,13 @@ def test_null_pointers_workspace_and_ranges(lib):
     assert lib.criticalkv_allocate(ctypes.byref(d), p, d.n_kv_heads * d.n_ctx + 1, 0.5, p, p, need, None) == P.CKV_E_INVALID_ARG
     assert lib.criticalkv_allocate(ctypes.byref(d), p, d.n_kv_heads * 1000, 0.0, p, p, 4096, None) == P.CKV_E_WORKSPACE
     assert P.workspace_bytes(d, 1000) > need
+    # diagnostics: pointers, budget range, modes without magnitudes or without the projection
+    assert lib.criticalkv_diagnostics(ctypes.byref(d), p, None, None, p, p, 100, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_diagnostics(ctypes.byref(d), p, p, None, p, p, 0, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_diagnostics(ctypes.byref(d), p, p, None, p, p, 1001, p, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_diagnostics(ctypes.byref(d), p, p, None, p, p, 100, p, p, 4096, None) == P.CKV_E_WORKSPACE
+    d_attn_only = good_desc(flags=P.CKV_ATTN_ONLY)
+    assert lib.criticalkv_diagnostics(ctypes.byref(d_attn_only), p, p, None, p, p, 100, p, p, need, None) == P.CKV_E_INVALID_ARG
     assert lib.criticalkv_compact(ctypes.byref(d), p, p, p, p, 0, p, p, None) == P.CKV_E_INVALID_ARG
     assert lib.criticalkv_compact(ctypes.byref(d), p, p, p, None, 10, p, p, None) == P.CKV_E_INVALID_ARG
 

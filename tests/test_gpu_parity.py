@@ -439,6 +439,103 @@ def test_allocate_then_select_on_llama_shape(P):
     assert np.array_equal(res2.count, got_on_gpu_scores)
 
 
+# ------------------------------------------------------------------------------------------------ diagnostics
+DIAG_TOL = 2e-3
+
+
+def run_diagnostics(P, cfg, t, budget, alpha, *, flags=0, wo_out_in=False, norm=1, window_reduce=None, own_vnorm=False,
+                    crit_is_attn=False):
+    """score -> select -> diagnostics through the C ABI; returns (out [b,H,8], idx, count)."""
+    import torch
+    if wo_out_in:
+        flags |= P.CKV_WO_OUT_IN
+    desc = cfg_desc(P, cfg, flags=flags, norm=norm, window_reduce=window_reduce)
+    dev = to_device(cfg, t, wo_out_in)
+    b, H, Hkv, n = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_ctx
+    budget = np.broadcast_to(np.asarray(budget, dtype=np.int32), (b, Hkv)).copy()
+    mb = max(1, int(budget.max()))
+    ws = torch.empty(P.workspace_bytes(desc, mb), dtype=torch.uint8, device="cuda")
+    attn = torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda")
+    crit = torch.empty_like(attn)
+    vnorm = torch.empty((b, H, n), dtype=torch.float32, device="cuda") if own_vnorm else None
+    idx = torch.empty((b, Hkv, mb), dtype=torch.int32, device="cuda")
+    count = torch.empty((b, Hkv), dtype=torch.int32, device="cuda")
+    out = torch.full((b, H, 8), -7.0, dtype=torch.float32, device="cuda")
+    P.criticalkv_score(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], attn, crit, vnorm, workspace=ws)
+    P.criticalkv_select(desc, attn, attn if crit_is_attn else crit, torch.from_numpy(budget).cuda(), alpha, mb, idx, count,
+                        workspace=ws)
+    P.criticalkv_diagnostics(desc, dev["v"], dev["w_o"], vnorm, idx, count, mb, out, workspace=ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64), idx.cpu().numpy(), count.cpu().numpy()
+
+
+def oracle_diagnostics(cfg, t, budget, alpha, norm=1, window_sum=False, crit_is_attn=False):
+    r = O.score(t["q_win"], t["k"], t["v"], t["w_o"], pool_kernel=cfg.pool_kernel, eps=cfg.eps, norm=norm)
+    idx, count, _, st1 = O.select(r.attn, r.attn if crit_is_attn else r.crit, budget, alpha, with_stage1=True)
+    return O.diagnostics(r.a_head, t["v"], t["w_o"], idx, count, st1, norm), idx
+
+
+def assert_diagnostics_close(got, ref, label):
+    """Every field is a sum of terms bounded by C (or a plain sum of A), so the error is measured against
+    max(|ref|, 1e-3 C); infinities must match exactly."""
+    f = {name: j for j, name in enumerate(O.DIAG_FIELDS)}
+    assert np.array_equal(np.isinf(got), np.isinf(ref)), label
+    fin = np.isfinite(ref)
+    scale = np.maximum(np.abs(ref), 1e-3 * ref[..., f["C"]][..., None])
+    for name in ("sigma", "s"):
+        scale[..., f[name]] = np.maximum(np.abs(ref[..., f[name]]), 1e-3)
+    rel = np.where(fin, np.abs(np.where(fin, got, 0) - np.where(fin, ref, 0)) / scale, 0.0)
+    worst = {name: float(rel[..., j].max()) for name, j in f.items()}
+    print(f"[diagnostics {label}] max scaled error per field: " + " ".join(f"{k}={v:.1e}" for k, v in worst.items()))
+    assert rel.max() <= DIAG_TOL, (label, worst)
+    return worst
+
+
+@pytest.mark.parametrize("case", ["tiny_f32", "llama_mfma", "llama_valu_outin", "qwen", "dh64_batch2", "l2", "own_vnorm"])
+def test_diagnostics_against_oracle(P, case):
+    kw, norm = {}, 1
+    if case == "tiny_f32":
+        cfg = CONFIGS["tiny"]
+    elif case == "qwen":
+        cfg = reduced(CONFIGS["qwen128k"], 3000, d_model=512)
+    elif case == "dh64_batch2":
+        cfg = reduced(CONFIGS["llama32k"], 1500, d_model=256, head_dim=64, batch=2)
+    else:
+        cfg = reduced(CONFIGS["llama32k"], 4133, d_model=512)
+    if case == "llama_valu_outin":
+        kw = dict(flags=P.CKV_NO_MFMA, wo_out_in=True)
+    if case == "l2":
+        norm = 2
+    if case == "own_vnorm":
+        kw = dict(own_vnorm=True)
+    t = make_layer(cfg)
+    got, idx, _ = run_diagnostics(P, cfg, t, cfg.budget, cfg.alpha, norm=norm, **kw)
+    ref, ref_idx = oracle_diagnostics(cfg, t, cfg.budget, cfg.alpha, norm=norm)
+    assert np.array_equal(idx, ref_idx)      # no swaps on these inputs, so both sides describe the same sets
+    assert_diagnostics_close(got, ref, case)
+    f = {name: j for j, name in enumerate(O.DIAG_FIELDS)}
+    assert np.all(got[..., f["L"]] <= got[..., f["theta"]] * (1 + 1e-4))
+    assert np.all(got[..., f["theta"]] <= got[..., f["theta_hat"]] * (1 + 1e-4))
+
+
+def test_diagnostics_special_budgets_and_baseline_selection(P):
+    cfg = reduced(CONFIGS["llama32k"], 2100, d_model=256)
+    t = make_layer(cfg)
+    n = cfg.n_ctx
+    # per-head budgets with an empty head and a full head; alpha = 0 leaves stage 1 empty, alpha = 1 stage 2
+    budgets = np.array([[0, 1, 7, 500, 1024, 1025, n - 1, n]])
+    for alpha in (0.5, 0.0, 1.0):
+        got, idx, _ = run_diagnostics(P, cfg, t, budgets, alpha)
+        ref, ref_idx = oracle_diagnostics(cfg, t, budgets, alpha)
+        assert np.array_equal(idx, ref_idx)
+        assert_diagnostics_close(got, ref, f"budgets alpha={alpha}")
+    # the attention-only baseline with the same split (stage 2 ranked by attention): its relaxed bound
+    got, idx, _ = run_diagnostics(P, cfg, t, cfg.budget, 0.5, crit_is_attn=True)
+    ref, ref_idx = oracle_diagnostics(cfg, t, cfg.budget, 0.5, crit_is_attn=True)
+    assert np.array_equal(idx, ref_idx)
+    assert_diagnostics_close(got, ref, "attention-only selection")
+
+
 # ------------------------------------------------------------------------------------------------ full-size
 def _full_size_check(P, cfg, t, sweeps=None, layer_label=""):
     """Full BASELINE shape in the launch configuration the benchmark times (output-major W_O).
