@@ -202,6 +202,14 @@ def main():
     serial_ms_per_step = (time.perf_counter() - s0) * 1e3 / args.steps
     stage_ms = {name: [] for name in P.STAGES}
     stage_ms["select"], stage_ms["compact"] = [], []
+    # rows beside the hot path, timed in the same untimed breakdown: adaptive budgets and the perturbation
+    # diagnostics (the latter needs the magnitudes and the projection itself, so only with --norm l1)
+    extras_ms = {"allocate": []}
+    with_diag = args.norm == "l1"
+    if with_diag:
+        extras_ms["diagnostics"] = []
+        diag_out = torch.empty((b, H, 8), dtype=torch.float32, device="cuda")
+    alloc_budget = torch.empty((b, Hkv), dtype=torch.int32, device="cuda")
     stream = lane0["stream"]
     sh = stream.cuda_stream or None
     for s in range(min(5, max(2, args.steps))):
@@ -212,6 +220,9 @@ def main():
         e_sel0, e_sel1, e_cp1 = ev.new(), ev.new(), ev.new()
         P.criticalkv_score_profiled(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], lane0["attn"], lane0["crit"], None,
                                     workspace=lane0["ws"], stage_events=arr, stream=stream)
+        e_al0 = ev.new()
+        ev.record(e_al0, sh)
+        P.criticalkv_allocate(desc, lane0["attn"], Hkv * B, 0.2, alloc_budget, workspace=lane0["ws"], stream=stream)
         ev.record(e_sel0, sh)
         P.criticalkv_select(desc, lane0["attn"], lane0["crit"], budget, cfg.alpha, B, lane0["idx"], lane0["count"],
                             workspace=lane0["ws"], stream=stream)
@@ -219,12 +230,26 @@ def main():
         P.criticalkv_compact(desc, dev["k"], dev["v"], lane0["idx"], lane0["count"], B, lane0["k_out"], lane0["v_out"],
                              stream=stream)
         ev.record(e_cp1, sh)
+        if with_diag:
+            e_dg1 = ev.new()
+            P.criticalkv_diagnostics(desc, dev["v"], dev["w_o"], None, lane0["idx"], lane0["count"], B, diag_out,
+                                     workspace=lane0["ws"], stream=stream)
+            ev.record(e_dg1, sh)
         torch.cuda.synchronize()
+        extras_ms["allocate"].append(ev.ms(e_al0, e_sel0))
+        if with_diag:
+            extras_ms["diagnostics"].append(ev.ms(e_cp1, e_dg1))
         for i, name in enumerate(P.STAGES):
             stage_ms[name].append(ev.ms(ctypes.c_void_p(arr[2 * i]), ctypes.c_void_p(arr[2 * i + 1])))
         stage_ms["select"].append(ev.ms(e_sel0, e_sel1))
         stage_ms["compact"].append(ev.ms(e_sel1, e_cp1))
     stage_ms = {k: round(float(np.median(v)), 4) for k, v in stage_ms.items()}
+    extras_ms = {k: round(float(np.median(v)), 4) for k, v in extras_ms.items()}
+    if with_diag:
+        dg = diag_out.double().cpu().numpy()
+        f = {name: j for j, name in enumerate(P.DIAG_FIELDS)}
+        extras_ms["diagnostics_mean_over_heads"] = {name: round(float(dg[..., j].mean()), 5) for name, j in f.items()}
+        extras_ms["heads_with_sigma_above_half"] = round(float((dg[..., f["sigma"]] > 0.5).mean()), 4)
     ev.close()
 
     entries = cfg.entries
@@ -256,7 +281,7 @@ def main():
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": VPROJ_TRAFFIC_BYTES.get(cfg.name) if args.norm == "l1" else None, "avg_launch_ms": round(vproj_avg, 4),
                      "algorithmic_flop_per_launch": flops},
-        "stages_ms": stage_ms,
+        "stages_ms": stage_ms, "beside_the_pass_ms": extras_ms,
         "pass_lower_bound_ms": round(t_bound_ms, 4), "pass_frac_of_bound": round(t_bound_ms / ms_per_step, 4),
     }
 

@@ -15,6 +15,8 @@
  *   - All tensor pointers are DEVICE pointers (HIP global memory) unless a
  *     parameter says "host".  Tensors are row-major with the last dimension
  *     contiguous.  The descriptor is a host struct and is read during the call.
+ *     Floating-point tensors (inputs and outputs) must start on a 16-byte
+ *     boundary (CKV_E_INVALID_ARG otherwise): rows are moved with vector accesses.
  *   - Ownership: the caller owns every buffer.  The library allocates nothing,
  *     frees nothing and keeps no pointer after a call returns; temporary device
  *     memory is the caller's `workspace` (size from criticalkv_workspace_bytes,

@@ -81,6 +81,9 @@ Workspace carve_workspace(const Dims &d, int dtype, bool need_wt, int max_budget
     return w;
 }
 
+// kernels read rows with 16-byte vector loads
+static bool misaligned16(const void *p) { return ((uintptr_t)p & 15) != 0; }
+
 static bool mfma_allowed(const ckv_layer_desc *desc)
 {
     return desc->dtype == CKV_BF16 && !(desc->flags & CKV_NO_MFMA);
@@ -116,6 +119,9 @@ static int score_impl(const ckv_layer_desc *desc, const void *q_win, const void 
     const bool attn_only = desc->flags & CKV_ATTN_ONLY;
     if (!q_win || !k || !attn || !crit || (!attn_only && (!v || !w_o))) return CKV_E_INVALID_ARG;
     if (attn_only && vnorm_opt) return CKV_E_INVALID_ARG; // no magnitudes are computed in this mode
+    if (misaligned16(q_win) || misaligned16(k) || misaligned16(v) || misaligned16(w_o) || misaligned16(attn) ||
+        misaligned16(crit) || misaligned16(vnorm_opt))
+        return CKV_E_INVALID_ARG;
     const bool have_gram = desc->flags & CKV_WO_IS_GRAM;
     if (have_gram && !(mfma_allowed(desc) && vproj_l2_mfma_supported(d))) return CKV_E_UNSUPPORTED;
     const bool need_wt = !attn_only && !have_gram && !(desc->flags & CKV_WO_OUT_IN);
@@ -211,6 +217,7 @@ int criticalkv_prepare_gram(const ckv_layer_desc *desc, const void *w_o, void *g
     int rc = resolve(desc, &d);
     if (rc != CKV_OK) return rc;
     if (!w_o || !gram_out || (desc->flags & CKV_WO_IS_GRAM)) return CKV_E_INVALID_ARG;
+    if (misaligned16(w_o) || misaligned16(gram_out)) return CKV_E_INVALID_ARG;
     if (desc->dtype != CKV_BF16 || !vproj_l2_mfma_supported(d)) return CKV_E_UNSUPPORTED;
     d.norm = CKV_NORM_L2; // the carve below must contain the Gram scratch whatever norm the descriptor names
     const bool need_wt = !(desc->flags & CKV_WO_OUT_IN);
@@ -234,6 +241,7 @@ int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float
     int rc = resolve(desc, &d);
     if (rc != CKV_OK) return rc;
     if (!attn || !crit || !budget || !idx || !count) return CKV_E_INVALID_ARG;
+    if (misaligned16(attn) || misaligned16(crit)) return CKV_E_INVALID_ARG;
     if (!(alpha >= 0.0f) || !(alpha <= 1.0f)) return CKV_E_INVALID_ARG;
     if (max_budget < 1 || max_budget > d.n) return CKV_E_INVALID_ARG;
     const Workspace ws = carve_workspace(d, desc->dtype, false, 0);
@@ -251,7 +259,7 @@ int criticalkv_allocate(const ckv_layer_desc *desc, const float *attn, int32_t t
     Dims d;
     int rc = resolve(desc, &d);
     if (rc != CKV_OK) return rc;
-    if (!attn || !budget) return CKV_E_INVALID_ARG;
+    if (!attn || !budget || misaligned16(attn)) return CKV_E_INVALID_ARG;
     if (total_budget < 0 || !(floor_frac >= 0.0f) || !(floor_frac <= 1.0f)) return CKV_E_INVALID_ARG;
     if ((int64_t)d.Hkv * d.n > (int64_t)INT32_MAX) return CKV_E_UNSUPPORTED;
     if ((int64_t)total_budget > (int64_t)d.Hkv * d.n) return CKV_E_INVALID_ARG;
@@ -275,6 +283,7 @@ int criticalkv_diagnostics(const ckv_layer_desc *desc, const void *v, const void
     int rc = resolve(desc, &d);
     if (rc != CKV_OK) return rc;
     if (!v || !w_o || !idx || !count || !out) return CKV_E_INVALID_ARG;
+    if (misaligned16(v) || misaligned16(w_o) || misaligned16(vnorm_opt)) return CKV_E_INVALID_ARG;
     if (desc->flags & (CKV_ATTN_ONLY | CKV_WO_IS_GRAM)) return CKV_E_INVALID_ARG; // needs the magnitudes and W_O itself
     if (max_budget < 1 || max_budget > d.n) return CKV_E_INVALID_ARG;
     const Workspace ws = carve_workspace(d, desc->dtype, false, 0); // the layout criticalkv_select used
@@ -295,6 +304,7 @@ int criticalkv_compact(const ckv_layer_desc *desc, const void *k, const void *v,
     int rc = resolve(desc, &d);
     if (rc != CKV_OK) return rc;
     if (!k || !v || !idx || !count || !k_out || !v_out) return CKV_E_INVALID_ARG;
+    if (misaligned16(k) || misaligned16(v) || misaligned16(k_out) || misaligned16(v_out)) return CKV_E_INVALID_ARG;
     if (max_budget < 1 || max_budget > d.n) return CKV_E_INVALID_ARG;
     hipError_t e = launch_compact(d, desc->dtype, k, v, idx, count, max_budget, k_out, v_out, (hipStream_t)hip_stream);
     return e == hipSuccess ? CKV_OK : CKV_E_HIP;

@@ -10,8 +10,8 @@
 // u_all = sum_i A_i v_i and u_S = sum_{S} A_i v_i: V is read once per kv head (plus the selected rows once
 // more) and W_O once per query head, instead of materialising V W_O.
 //
-//   sweep     one workgroup per (1024-token chunk, kv head): partial u_all, C, M for the group's query heads
-//   selected  one workgroup per (1024-entry chunk of the index list, kv head): partial u_S and the four
+//   sweep     one workgroup per (256-token chunk, kv head): partial u_all, C, M for the group's query heads
+//   selected  one workgroup per (256-entry chunk of the index list, kv head): partial u_S and the four
 //             sums over S1 / S2; stage-1 membership is read from the selection's stage-2 key array
 //   finish    one workgroup per query head: chunk partials summed in double in a fixed order, the
 //             d_h x d matrix-vector product, the norm of the result and the closed forms
@@ -20,7 +20,7 @@
 namespace ckv {
 
 constexpr int DG_THREADS = 256;
-constexpr int DG_CHUNK = 1024;
+constexpr int DG_CHUNK = 256;
 constexpr int DG_GMAX = 8; // query heads of a group handled by one workgroup (more: blockIdx.z)
 constexpr uint32_t DG_TAKEN = 0xFFFFFFFFu; // the selection's mark for stage-1 entries in its stage-2 keys
 
@@ -74,7 +74,24 @@ __device__ __forceinline__ float block_min_f32(float x, float *sh)
     return sh[0];
 }
 
-// SELECTED = false: tokens [chunk * 1024, ...) of the head.  SELECTED = true: entries j of the index list.
+// 8 consecutive elements of a row as floats (rows start on 16-byte boundaries, groups of 8 stay aligned)
+__device__ __forceinline__ void load8_f32(const bf16_t *p, float (&x)[8])
+{
+    const uint4 r = *reinterpret_cast<const uint4 *>(p);
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[2 * e] = __uint_as_float(w[e] << 16);
+        x[2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
+    }
+}
+__device__ __forceinline__ void load8_f32(const float *p, float (&x)[8])
+{
+    const float4 a = *reinterpret_cast<const float4 *>(p), b = *reinterpret_cast<const float4 *>(p + 4);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+
+// SELECTED = false: tokens [chunk * 256, ...) of the head.  SELECTED = true: entries j of the index list.
 template <typename T, bool SELECTED>
 __global__ __launch_bounds__(DG_THREADS) void diag_partial_kernel(DiagArgs A)
 {
@@ -82,7 +99,7 @@ __global__ __launch_bounds__(DG_THREADS) void diag_partial_kernel(DiagArgs A)
     __shared__ int tok_s[DG_CHUNK];            // SELECTED: token index (-1 = skip); stage-1 flag in st1_s
     __shared__ unsigned char st1_s[DG_CHUNK];
     __shared__ float red_s[DG_THREADS];
-    __shared__ float u_s[DG_THREADS];
+    __shared__ float u_s[DG_THREADS * 8]; // [row lanes][dh]
 
     const int chunk = blockIdx.x, head = blockIdx.y; // head = bi * Hkv + g
     const int bi = head / A.Hkv, g = head % A.Hkv;
@@ -141,36 +158,47 @@ __global__ __launch_bounds__(DG_THREADS) void diag_partial_kernel(DiagArgs A)
         }
     }
 
-    // weighted value sums: thread = (token lane, column)
-    const int col = threadIdx.x % A.dh, lane = threadIdx.x / A.dh, lanes = DG_THREADS / A.dh;
-    float acc[DG_GMAX];
+    // weighted value sums: thread = (row lane, group of 8 columns); one 16-byte (bf16) or 32-byte (f32) load per row
+    const int groups = A.dh >> 3, cg = threadIdx.x % groups, lane = threadIdx.x / groups, lanes = DG_THREADS / groups;
+    float acc[DG_GMAX][8];
 #pragma unroll
-    for (int hh = 0; hh < DG_GMAX; ++hh) acc[hh] = 0.0f;
+    for (int hh = 0; hh < DG_GMAX; ++hh)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
     if (!empty) {
-        const T *vb = reinterpret_cast<const T *>(A.v) + bi * A.vs0 + g * A.vs1;
+        const T *vb = reinterpret_cast<const T *>(A.v) + bi * A.vs0 + g * A.vs1 + cg * 8;
+#pragma unroll 4
         for (int jj = lane; jj < len; jj += lanes) {
             const int i = tok_s[jj];
-            if (i < 0) continue;
-            const float x = to_f32(vb[(int64_t)i * A.vs2 + col]);
+            float x[8];
+            if (i >= 0) load8_f32(vb + (int64_t)i * A.vs2, x);
+            else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = 0.0f;
+            }
 #pragma unroll
             for (int hh = 0; hh < DG_GMAX; ++hh)
-                if (hh < gc) acc[hh] += a_s[hh][jj] * x;
+                if (hh < gc) {
+                    const float a = a_s[hh][jj];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[hh][e] += a * x[e];
+                }
         }
     }
-    for (int hh = 0; hh < gc; ++hh) {
-        float x = 0.0f;
 #pragma unroll
-        for (int q = 0; q < DG_GMAX; ++q)
-            if (q == hh) x = acc[q];
-        __syncthreads();
-        u_s[threadIdx.x] = x;
-        __syncthreads();
-        if ((int)threadIdx.x < A.dh) {
-            float sum = 0.0f;
-            for (int l = 0; l < lanes; ++l) sum += u_s[l * A.dh + threadIdx.x];
-            float *dst = SELECTED ? A.part_sel + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 4)
-                                  : A.part_all + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 2);
-            dst[threadIdx.x] = sum;
+    for (int hh = 0; hh < DG_GMAX; ++hh) {
+        if (hh < gc) { // uniform over the workgroup
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < 8; ++e) u_s[lane * A.dh + cg * 8 + e] = acc[hh][e];
+            __syncthreads();
+            if ((int)threadIdx.x < A.dh) {
+                float sum = 0.0f;
+                for (int l = 0; l < lanes; ++l) sum += u_s[l * A.dh + threadIdx.x];
+                float *dst = SELECTED ? A.part_sel + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 4)
+                                      : A.part_all + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 2);
+                dst[threadIdx.x] = sum;
+            }
         }
     }
 }
@@ -220,8 +248,13 @@ __global__ __launch_bounds__(DG_THREADS) void diag_finish_kernel(DiagArgs A, con
     for (int m = threadIdx.x; m < dm; m += DG_THREADS) {
         double y = 0.0;
         if (out_in) {
-            const T *row = w + (size_t)m * ((size_t)A.H * A.dh) + (size_t)h * A.dh;
-            for (int c = 0; c < A.dh; ++c) y += diff_s[c] * (double)to_f32(row[c]);
+            const T *row = w + (size_t)m * ((size_t)A.H * A.dh) + (size_t)h * A.dh; // 16-byte aligned: dh is a multiple of 64
+            for (int c = 0; c < A.dh; c += 8) {
+                float x[8];
+                load8_f32(row + c, x);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) y += diff_s[c + e] * (double)x[e];
+            }
         } else {
             const T *colp = w + (size_t)h * A.dh * dm + m;
             for (int c = 0; c < A.dh; ++c) y += diff_s[c] * (double)to_f32(colp[(size_t)c * dm]);

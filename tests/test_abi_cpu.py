@@ -89,6 +89,10 @@ def test_null_pointers_workspace_and_ranges(lib):
     # null tensor
     assert lib.criticalkv_score(ctypes.byref(d), None, p, p, p, p, p, None, p, need, None) == P.CKV_E_INVALID_ARG
     assert lib.criticalkv_score(None, p, p, p, p, p, p, None, p, need, None) == P.CKV_E_INVALID_ARG
+    # a tensor that does not start on a 16-byte boundary
+    assert lib.criticalkv_score(ctypes.byref(d), p, p + 8, p, p, p, p, None, p, need, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_compact(ctypes.byref(d), p, p + 2, p, p, 10, p, p, None) == P.CKV_E_INVALID_ARG
+    assert lib.criticalkv_select(ctypes.byref(d), p + 4, p, p, 0.5, 100, p, p, p, need, None) == P.CKV_E_INVALID_ARG
     # workspace missing / misaligned / too small
     assert lib.criticalkv_score(ctypes.byref(d), p, p, p, p, p, p, None, None, need, None) == P.CKV_E_WORKSPACE
     assert lib.criticalkv_score(ctypes.byref(d), p, p, p, p, p, p, None, p + 8, need, None) == P.CKV_E_WORKSPACE

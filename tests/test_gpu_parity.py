@@ -563,6 +563,12 @@ def _full_size_check(P, cfg, t, sweeps=None, layer_label=""):
     assert not np.array_equal(top_idx, ref_idx)
     print(f"[{cfg.name}{layer_label} full] max rel err attn {e_a[0]:.2e} vnorm {e_v[0]:.2e} crit {e_c[0]:.2e} "
           f"on {rows.size} sampled tokens; selection exact on {cfg.batch * cfg.n_kv_heads} heads")
+    # adaptive budgets over the whole layer: one row of Hkv * n keys per batch item, exact on the GPU's own keys
+    total = cfg.n_kv_heads * cfg.budget
+    for ff in (np.float32(0.2), np.float32(0.0)):
+        got_b = run_allocate(P, res.attn, total, ff)
+        assert np.array_equal(got_b, O.allocate(res.attn.astype(np.float64), total, ff)), ff
+    print(f"[{cfg.name}{layer_label} full] allocated budgets (floor 0): {got_b.tolist()}")
     for B, alpha in (sweeps or []):
         idx, count, _ = run_select(P, res.attn, res.crit, B, alpha)
         ref_idx, ref_count, _ = O.select(res.attn.astype(np.float64), res.crit.astype(np.float64), B, np.float32(alpha))
@@ -574,6 +580,26 @@ def _full_size_check(P, cfg, t, sweeps=None, layer_label=""):
 def test_full_size_llama32k(P):
     cfg = CONFIGS["llama32k"]
     _full_size_check(P, cfg, make_layer(cfg))
+
+
+def test_full_size_diagnostics_one_kv_group_llama32k(P):
+    """Full shape on the GPU; the oracle computes the last kv head's group alone (its queries, keys, values and
+    W_O rows), which is the part of the output one can afford to check one by one."""
+    cfg = CONFIGS["llama32k"]
+    t = make_layer(cfg)
+    got, idx, _ = run_diagnostics(P, cfg, t, cfg.budget, cfg.alpha, wo_out_in=True)
+    G = cfg.n_q_heads // cfg.n_kv_heads
+    g = cfg.n_kv_heads - 1
+    hs = slice(g * G, (g + 1) * G)
+    sub = {"q_win": t["q_win"][:, hs], "k": t["k"][:, g:g + 1], "v": t["v"][:, g:g + 1],
+           "w_o": t["w_o"][g * G * cfg.head_dim:(g + 1) * G * cfg.head_dim]}
+    ref, ref_idx = oracle_diagnostics(cfg, sub, cfg.budget, cfg.alpha)
+    assert np.array_equal(idx[:, g:g + 1], ref_idx)
+    assert_diagnostics_close(got[:, hs], ref, "llama32k full, last kv group")
+    f = {name: j for j, name in enumerate(O.DIAG_FIELDS)}
+    assert np.all(got[..., f["L"]] <= got[..., f["theta"]]) and np.all(got[..., f["theta"]] <= got[..., f["theta_hat"]] * (1 + 1e-5))
+    print(f"[llama32k full] heads with sigma > 0.5: {(got[..., f['sigma']] > 0.5).mean():.3f}; mean L {got[..., f['L']].mean():.4f} "
+          f"theta_hat {got[..., f['theta_hat']].mean():.4f} theta_relax {got[..., f['theta_relax']].mean():.4f}")
 
 
 def test_full_size_llama128k(P):
