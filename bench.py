@@ -244,6 +244,36 @@ def main():
         stage_ms["select"].append(ev.ms(e_sel0, e_sel1))
         stage_ms["compact"].append(ev.ms(e_sel1, e_cp1))
     stage_ms = {k: round(float(np.median(v)), 4) for k, v in stage_ms.items()}
+    # the same steps replayed from HIP graphs (one captured pass per input set): the launch-bound tail of small
+    # kernels is issued without per-kernel host dispatch.  Untimed extra: events recorded inside a captured graph
+    # carry no timing on replay, so the headline stays on the eager steps whose projection kernel is event-marked.
+    graph_ms = None
+    try:
+        graphs = []
+        with torch.cuda.stream(stream):
+            for dev in sets:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    cur = torch.cuda.current_stream()
+                    P.criticalkv_score(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], lane0["attn"], lane0["crit"], None,
+                                       workspace=lane0["ws"], stream=cur)
+                    P.criticalkv_select(desc, lane0["attn"], lane0["crit"], budget, cfg.alpha, B, lane0["idx"], lane0["count"],
+                                        workspace=lane0["ws"], stream=cur)
+                    P.criticalkv_compact(desc, dev["k"], dev["v"], lane0["idx"], lane0["count"], B, lane0["k_out"],
+                                         lane0["v_out"], stream=cur)
+                graphs.append(g)
+            for w in range(args.warmup):
+                graphs[w % nsets].replay()
+            torch.cuda.synchronize()
+            g0 = time.perf_counter()
+            for s in range(args.steps):
+                graphs[s % nsets].replay()
+            torch.cuda.synchronize()
+            graph_ms = round((time.perf_counter() - g0) * 1e3 / args.steps, 4)
+        assert int(lane0["count"].min()) == B
+        del graphs
+    except RuntimeError as exc:  # capture not available: report it, the headline does not depend on it
+        graph_ms = f"unavailable: {exc}"
     extras_ms = {k: round(float(np.median(v)), 4) for k, v in extras_ms.items()}
     if with_diag:
         dg = diag_out.double().cpu().numpy()
@@ -274,6 +304,7 @@ def main():
                                f"W {cfg.window}, pool {cfg.pool_kernel}, budget {B}/head, alpha {cfg.alpha}, norm {args.norm}",
                    "w_o_layout": "[d_model, H*d_h] (CKV_WO_OUT_IN)", "input_sets_rotated": nsets,
                    "streams": n_streams, "serial_ms_per_step": round(serial_ms_per_step, 4),
+                   "graph_replay_ms_per_step": graph_ms,
                    "tokens_per_s": round(b * n / (ms_per_step * 1e-3), 1),
                    **({"layers": cfg.n_layers, "total_ms_all_layers": round(cfg.n_layers * ms_per_step, 3)}
                       if cfg.n_layers > 1 else {})},

@@ -134,7 +134,9 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
             for (int s = 0; s < VM_KS; ++s) {
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) {
-                    if (s == 1 && rb == 0) issue_load(tn, cb, nxt);
+                    // the next tile's loads go out early in this tile (its buffer is idle since the last barrier),
+                    // so that they have landed long before the barrier at the end
+                    if (cb < VM_CB / 2 && (s == 1 || s == 3) && rb == 0) issue_load(tn, 2 * cb + (s >> 1), nxt);
                     // RB independent accumulator chains, taken in turns (a chain's next link is RB MFMAs later)
                     if (s == 0)
                         acc[pp][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rb][s], b[s], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);

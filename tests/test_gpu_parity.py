@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from helpers import (assert_compaction_exact, assert_scores_close, cfg_desc, compare_selection, run_gpu_pass,
-                     to_device)
+                     to_device)  # noqa: F401
 from oracle import cpu_oracle as O
 from workload import CONFIGS, make_layer, reduced
 
@@ -621,6 +621,60 @@ def test_full_size_mistral_prefill_layer(P, layer):
 
 
 # ------------------------------------------------------------------------------------------------ runtime plumbing
+def test_pass_replays_from_a_hip_graph(P):
+    """score -> select -> compact captured once and replayed with new input values in the same buffers; eager
+    work and synchronisations sit between the replays, and every replay must equal the eager result bit for bit
+    (the pass enqueues kernels only: no memset nodes, no host synchronisation, no allocation)."""
+    import torch
+    cfg = reduced(CONFIGS["llama32k"], 4133, d_model=512)
+    desc = cfg_desc(P, cfg, flags=P.CKV_WO_OUT_IN)
+    b, H, Hkv, n, dh, B = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_ctx, cfg.head_dim, cfg.budget
+    layers = [to_device(cfg, make_layer(cfg, layer=0, seed_offset=s), True) for s in range(3)]
+    buf = {k: torch.empty_like(v) for k, v in layers[0].items()}
+
+    def outputs():
+        return dict(attn=torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda"),
+                    crit=torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda"),
+                    idx=torch.empty((b, Hkv, B), dtype=torch.int32, device="cuda"),
+                    count=torch.empty((b, Hkv), dtype=torch.int32, device="cuda"),
+                    k_out=torch.zeros((b, Hkv, B, dh), dtype=torch.bfloat16, device="cuda"),
+                    v_out=torch.zeros((b, Hkv, B, dh), dtype=torch.bfloat16, device="cuda"),
+                    ws=torch.empty(P.workspace_bytes(desc, B), dtype=torch.uint8, device="cuda"))
+    budget = torch.full((b, Hkv), B, dtype=torch.int32, device="cuda")
+
+    def one_pass(o, stream):
+        P.criticalkv_score(desc, buf["q_win"], buf["k"], buf["v"], buf["w_o"], o["attn"], o["crit"], None, workspace=o["ws"],
+                           stream=stream)
+        P.criticalkv_select(desc, o["attn"], o["crit"], budget, cfg.alpha, B, o["idx"], o["count"], workspace=o["ws"],
+                            stream=stream)
+        P.criticalkv_compact(desc, buf["k"], buf["v"], o["idx"], o["count"], B, o["k_out"], o["v_out"], stream=stream)
+
+    eager, replayed = outputs(), outputs()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        for k in buf:
+            buf[k].copy_(layers[0][k])
+        one_pass(replayed, st)            # warm-up outside the capture
+        st.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            one_pass(replayed, torch.cuda.current_stream())
+        for r in (1, 2, 0, 1):
+            for k in buf:
+                buf[k].copy_(layers[r][k])
+            one_pass(eager, st)           # the program's own eager work between replays
+            st.synchronize()
+            for t in ("idx", "k_out", "v_out", "attn", "crit"):
+                replayed[t].fill_(0)      # a replay must rewrite everything it owns
+            g.replay()
+            torch.cuda.synchronize()
+            for t in ("attn", "crit", "idx", "count", "k_out", "v_out"):
+                assert torch.equal(eager[t], replayed[t]), (r, t)
+    ref = O.full_pass(*(make_layer(cfg, layer=0, seed_offset=1)[k] for k in ("q_win", "k", "v", "w_o")), B, cfg.alpha,
+                      pool_kernel=cfg.pool_kernel, eps=cfg.eps)
+    compare_selection(replayed["idx"].cpu().numpy(), replayed["count"].cpu().numpy(), ref, B, cfg.alpha)
+
+
 def test_single_hip_runtime_and_side_stream(P):
     """The library must run in PyTorch's HIP runtime (one libamdhip64 mapped) and honour a non-default stream."""
     import torch
