@@ -9,10 +9,11 @@
 //                 this is a per-layer constant, a few GFLOP)
 //   gram_finish   sums the slices and splits G into two bf16 matrices G_hi + G_lo (error ~2^-17 relative),
 //                 stored [head][u][t] (G is symmetric, so a row is also a column)
-//   l2 kernel     one workgroup per (row tile, kv head): the V rows stay in registers as MFMA B fragments
-//                 for all G query heads of the group (V is read once); per head the two G matrices (64 KiB)
-//                 are brought into LDS and  Y^T = G V^T  is accumulated with v_mfma_f32_16x16x32_bf16 over
-//                 G_hi and G_lo; the epilogue multiplies by v again:  N^2_i = sum_u Y[i,u] v[i,u].
+//   l2 kernel     one workgroup per (group of row tiles, kv head): a tile's V rows stay in registers as MFMA
+//                 B fragments for all G query heads of the group (V is read once); per head the two G
+//                 matrices (64 KiB) stream through a double-buffered LDS and  Y^T = G V^T  is accumulated
+//                 with v_mfma_f32_16x16x32_bf16 over G_hi and G_lo; the epilogue multiplies by v again:
+//                 N^2_i = sum_u Y[i,u] v[i,u].
 #include "common.hpp"
 
 namespace ckv {
@@ -23,8 +24,9 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int GL_DH = 128;
 constexpr int GL_SLICES = 4;          // d_model slices of the Gram partial sums
 constexpr int GL_TILE_C = 128;        // columns of W_O staged per LDS tile in gram_partial
-constexpr int GL_WAVES = 4;
-constexpr int GL_RB = 6;              // 16-row blocks per wave
+constexpr int GL_WAVES = 8;            // one workgroup of 8 waves per CU
+constexpr int GL_THREADS = GL_WAVES * 64;
+constexpr int GL_RB = 4;              // 16-row blocks per wave and row tile
 constexpr int GL_G_BYTES = GL_DH * GL_DH * 2; // one bf16 Gram matrix: 32 KiB
 
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -96,81 +98,124 @@ __global__ __launch_bounds__(256) void gram_finish_kernel(const float *__restric
     }
 }
 
-// N^h_i for the G query heads of one kv head and one tile of 4 waves x GL_RB x 16 rows.
-__global__ __launch_bounds__(256, 2) void vproj_l2_mfma_kernel(const bf16_t *__restrict__ v, const bf16_t *__restrict__ gram,
-                                                               float *__restrict__ vnorm, int H, int G, int n,
-                                                               int64_t vs0, int64_t vs1, int64_t vs2)
+// N^h_i for the G query heads of one kv head and `passes` row tiles of 8 waves x GL_RB x 16 rows.
+//
+// One workgroup of 8 waves per CU.  The work of a workgroup is a sequence of steps (row tile, query head);
+// a step needs that head's two Gram matrices (64 KiB) in LDS.  The matrices are double buffered (128 KiB):
+// the loads of step k + 1 are issued before the MFMAs of step k and are waited for after them, so one barrier
+// per step is the only synchronisation and the L2 latency of the matrices hides behind 256 MFMAs per wave.
+// A row tile's V fragments stay in registers for its G steps.
+__global__ __launch_bounds__(GL_THREADS) void vproj_l2_mfma_kernel(const bf16_t *__restrict__ v,
+                                                                    const bf16_t *__restrict__ gram,
+                                                                    float *__restrict__ vnorm, int H, int G, int n,
+                                                                    int64_t vs0, int64_t vs1, int64_t vs2, int passes)
 {
-    __shared__ __attribute__((aligned(1024))) char lds[2 * GL_G_BYTES]; // G_hi | G_lo, 16-byte chunks XOR-swizzled
+    __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * GL_G_BYTES]; // 2 buffers x (G_hi | G_lo), XOR-swizzled
     const int Hkv = H / G;
     const int g = blockIdx.y % Hkv, bi = blockIdx.y / Hkv;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, kc = lane >> 4;
-    const int row0 = (blockIdx.x * GL_WAVES + wave) * (GL_RB * 16);
-
-    // B fragments: this wave's rows of V (token i = lane % 16 of block rb, k = t)
-    bf16x8 vf[GL_RB][4];
+    const int rows_per_pass = GL_WAVES * GL_RB * 16;
+    const int tile_row0 = blockIdx.x * passes * rows_per_pass;
+    // row tiles that start inside the head (a uniform count: all waves take the same number of barriers)
+    const int my_passes = min(passes, (n - tile_row0 + rows_per_pass - 1) / rows_per_pass);
+    const int steps = my_passes * G;
     const bf16_t *vbase = v + bi * vs0 + g * vs1;
-#pragma unroll
-    for (int rb = 0; rb < GL_RB; ++rb) {
-        const int row = min(row0 + rb * 16 + l16, n - 1);
-        const bf16_t *p = vbase + (int64_t)row * vs2 + kc * 8;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) vf[rb][s] = *reinterpret_cast<const bf16x8 *>(p + s * 32);
-    }
 
-    for (int hl = 0; hl < G; ++hl) {
-        const int h = g * G + hl;
-        // G_hi and G_lo of this head: 64 KiB = 64 direct loads of 1 KiB, 16 per wave.  Row u of a matrix is
-        // 256 B = 16 chunks; chunk q is stored at slot q ^ (u & 15).
-        __syncthreads(); // every wave is done with the previous head's matrices
-        {
-            const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)(gram + (size_t)h * 2 * GL_DH * GL_DH), 0, 2 * GL_G_BYTES, 0x00020000);
+    // 64 KiB of one head = 64 direct loads of 1 KiB, 8 per wave.  Row u of a matrix is 256 B = 16 chunks;
+    // chunk q is stored at slot q ^ f(u), f(u) = 4 * ((u / 8) % 4) + u % 4: the 16 rows that one MFMA A operand
+    // reads together (see below) have 16 different f, so their 16-byte reads fall on different banks.
+    auto issue_gram = [&](int step, int buf) {
+        const int h = g * G + step % G;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(gram + (size_t)h * 2 * GL_DH * GL_DH), 0, 2 * GL_G_BYTES, 0x00020000);
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int kib = j * GL_WAVES + wave;            // KiB index inside the 64 KiB: rows 4*kib .. 4*kib+3
-                const int urow = (kib * 4 + (lane >> 4)) & (GL_DH - 1);
-                const uint32_t voff = (uint32_t)(kib * 1024 + (lane >> 4) * 256 + (((lane & 15) ^ (urow & 15)) * 16));
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(lds + kib * 1024), 16, voff, 0, 0, 0);
-            }
+        for (int j = 0; j < 64 / GL_WAVES; ++j) {
+            const int kib = j * GL_WAVES + wave;            // KiB index inside the 64 KiB: rows 4*kib .. 4*kib+3
+            const int urow = (kib * 4 + (lane >> 4)) & (GL_DH - 1);
+            const int f = ((urow >> 3) & 3) * 4 + (urow & 3);
+            const uint32_t voff = (uint32_t)(kib * 1024 + (lane >> 4) * 256 + (((lane & 15) ^ f) * 16));
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(lds + buf * 2 * GL_G_BYTES + kib * 1024), 16, voff, 0, 0, 0);
         }
-        __syncthreads();
+    };
+    // B fragments: this wave's rows of V (token i = lane % 16 of block rb, k = t)
+    auto load_v = [&](int pass, bf16x8 (&dst)[GL_RB][4]) {
+        const int row0 = tile_row0 + (pass * GL_WAVES + wave) * (GL_RB * 16);
+#pragma unroll
+        for (int rb = 0; rb < GL_RB; ++rb) {
+            const int row = min(row0 + rb * 16 + l16, n - 1);
+            const bf16_t *p = vbase + (int64_t)row * vs2 + kc * 8;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) dst[rb][s] = *reinterpret_cast<const bf16x8 *>(p + s * 32);
+        }
+    };
+
+    if (steps <= 0) return; // uniform over the workgroup
+    bf16x8 vf[GL_RB][4];
+    issue_gram(0, 0);
+    load_v(0, vf);
+    __syncthreads(); // waits for the direct loads of this wave, then for every wave
+
+#pragma unroll 1
+    for (int step = 0; step < steps; ++step) {
+        const int pass = step / G, hl = step - pass * G, buf = step & 1;
+        if (step + 1 < steps) issue_gram(step + 1, buf ^ 1); // that buffer was last read in step - 1
+        const char *gl = lds + buf * 2 * GL_G_BYTES;
+        const int row0 = tile_row0 + (pass * GL_WAVES + wave) * (GL_RB * 16);
 
         float nsq[GL_RB];
 #pragma unroll
         for (int rb = 0; rb < GL_RB; ++rb) nsq[rb] = 0.f;
-#pragma unroll 1
-        for (int ub = 0; ub < GL_DH / 16; ++ub) {
-            // A fragments: rows u = 16*ub + lane%16 of G_hi / G_lo, k = t
-            bf16x8 ghi[4], glo[4];
-            const char *rowp = lds + (ub * 16 + l16) * 256;
+        // The 16 rows u of G that one MFMA takes as its A operand are chosen so that the product's epilogue factor
+        // v[i][u] is already in the lane's registers: accumulator value j of lane (i, kc) belongs to A row
+        // m = 4 * kc + j, and that row is u(m) = 32 * sp + 8 * (m / 4) + 4 * half + m % 4 = 32 * sp + 8 * kc + 4 * half + j,
+        // i.e. element 4 * half + j of the lane's own fragment vf[rb][sp].  (sp, half) = (ub / 2, ub % 2) covers all rows.
+        const int a_row = 8 * (l16 >> 2) + (l16 & 3);          // + 32 * sp + 4 * half
+        const int a_f = 4 * (l16 >> 2) + (l16 & 3);            // f(u) of that row: bits 3-4 and 0-1 of u
+        // fragments of 16 rows of G_hi (0-3) and G_lo (4-7); read one ub ahead of their use
+        bf16x8 gf[2][8];
+        auto read_g = [&](int ub, bf16x8 (&dst)[8]) {
+            const char *rowp = gl + (32 * (ub >> 1) + 4 * (ub & 1) + a_row) * 256;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const int slot = ((4 * s + kc) ^ l16) * 16;
-                ghi[s] = *reinterpret_cast<const bf16x8 *>(rowp + slot);
-                glo[s] = *reinterpret_cast<const bf16x8 *>(rowp + GL_G_BYTES + slot);
+                const int slot = ((4 * s + kc) ^ a_f) * 16;
+                dst[s] = *reinterpret_cast<const bf16x8 *>(rowp + slot);
+                dst[4 + s] = *reinterpret_cast<const bf16x8 *>(rowp + GL_G_BYTES + slot);
+            }
+        };
+        read_g(0, gf[0]);
+#pragma unroll
+        for (int ub = 0; ub < GL_DH / 16; ++ub) {
+            const int sp = ub >> 1, half = ub & 1, cur = ub & 1;
+            if (ub + 1 < GL_DH / 16) read_g(ub + 1, gf[cur ^ 1]);
+            // GL_RB independent accumulator chains taken in turns
+            f32x4 acc[GL_RB];
+#pragma unroll
+            for (int rb = 0; rb < GL_RB; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+#pragma unroll
+                for (int rb = 0; rb < GL_RB; ++rb)
+                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gf[cur][4 + s], vf[rb][s], acc[rb], 0, 0, 0);
+#pragma unroll
+                for (int rb = 0; rb < GL_RB; ++rb)
+                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gf[cur][s], vf[rb][s], acc[rb], 0, 0, 0);
             }
 #pragma unroll
             for (int rb = 0; rb < GL_RB; ++rb) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(glo[s], vf[rb][s], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ghi[s], vf[rb][s], acc, 0, 0, 0);
-                }
-                // acc[j] = Y[i][u] for token i = rb*16 + lane%16, u = 16*ub + 4*kc + j; multiply by v[i][u]
-                const int row = min(row0 + rb * 16 + l16, n - 1);
-                const uint2 raw = *reinterpret_cast<const uint2 *>(vbase + (int64_t)row * vs2 + ub * 16 + kc * 4);
-                nsq[rb] = fmaf(acc[0], __uint_as_float(raw.x << 16), nsq[rb]);
-                nsq[rb] = fmaf(acc[1], __uint_as_float(raw.x & 0xFFFF0000u), nsq[rb]);
-                nsq[rb] = fmaf(acc[2], __uint_as_float(raw.y << 16), nsq[rb]);
-                nsq[rb] = fmaf(acc[3], __uint_as_float(raw.y & 0xFFFF0000u), nsq[rb]);
+                typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+                const u32x4 w = __builtin_bit_cast(u32x4, vf[rb][sp]);
+                const uint32_t w0 = w[2 * half], w1 = w[2 * half + 1];
+                nsq[rb] = fmaf(acc[rb][0], __uint_as_float(w0 << 16), nsq[rb]);
+                nsq[rb] = fmaf(acc[rb][1], __uint_as_float(w0 & 0xFFFF0000u), nsq[rb]);
+                nsq[rb] = fmaf(acc[rb][2], __uint_as_float(w1 << 16), nsq[rb]);
+                nsq[rb] = fmaf(acc[rb][3], __uint_as_float(w1 & 0xFFFF0000u), nsq[rb]);
             }
+            __builtin_amdgcn_sched_barrier(0); // keep the read-ahead distance at one ub (registers)
         }
         // merge the four k-chunk lanes of a token, then one value per token
-        float *out = vnorm + ((size_t)bi * H + h) * (size_t)n;
+        float *out = vnorm + ((size_t)bi * H + g * G + hl) * (size_t)n;
 #pragma unroll
         for (int rb = 0; rb < GL_RB; ++rb) {
             float x = nsq[rb];
@@ -179,6 +224,9 @@ __global__ __launch_bounds__(256, 2) void vproj_l2_mfma_kernel(const bf16_t *__r
             const int row = row0 + rb * 16 + l16;
             if (kc == 0 && row < n) out[row] = sqrtf(fmaxf(x, 0.f));
         }
+        // the next row tile's fragments replace this one's after its last step (they are waited for with the barrier)
+        if (hl == G - 1 && pass + 1 < my_passes) load_v(pass + 1, vf);
+        __syncthreads(); // the next step's matrices have landed (own loads waited first) and this buffer is free
     }
 }
 
@@ -202,10 +250,16 @@ hipError_t launch_gram(const Dims &d, const void *w_t, void *gram_out, void *par
 
 hipError_t launch_vproj_l2_mfma(const Dims &d, const void *v, const void *gram, float *vnorm, hipStream_t s)
 {
-    const int rows_per_wg = GL_WAVES * GL_RB * 16;
+    // row tiles per workgroup: aim at one workgroup per CU (256) for the whole launch, so that every CU streams
+    // the Gram matrices the same number of times and the launch has no partial last round
+    const int rows_per_pass = GL_WAVES * GL_RB * 16;
+    const long long total_rows = (long long)d.batch * d.Hkv * d.n;
+    int passes = (int)((total_rows + 128ll * rows_per_pass) / (256ll * rows_per_pass));
+    passes = passes < 1 ? 1 : passes > 64 ? 64 : passes;
+    const int rows_per_wg = passes * rows_per_pass;
     dim3 grid((d.n + rows_per_wg - 1) / rows_per_wg, d.batch * d.Hkv);
-    hipLaunchKernelGGL(vproj_l2_mfma_kernel, grid, dim3(256), 0, s, (const bf16_t *)v, (const bf16_t *)gram, vnorm, d.H,
-                       d.G, d.n, d.vs[0], d.vs[1], d.vs[2]);
+    hipLaunchKernelGGL(vproj_l2_mfma_kernel, grid, dim3(GL_THREADS), 0, s, (const bf16_t *)v, (const bf16_t *)gram, vnorm,
+                       d.H, d.G, d.n, d.vs[0], d.vs[1], d.vs[2], passes);
     return hipGetLastError();
 }
 
