@@ -10,17 +10,19 @@
 // u_all = sum_i A_i v_i and u_S = sum_{S} A_i v_i: V is read once per kv head (plus the selected rows once
 // more) and W_O once per query head, instead of materialising V W_O.
 //
-//   sweep     one workgroup per (256-token chunk, kv head): partial u_all, C, M for the group's query heads
-//   selected  one workgroup per (256-entry chunk of the index list, kv head): partial u_S and the four
-//             sums over S1 / S2; stage-1 membership is read from the selection's stage-2 key array
-//   finish    one workgroup per query head: chunk partials summed in double in a fixed order, the
+//   sweep     32 workgroups per kv head, each over every 32nd 256-token chunk: partial u_all, C, M for the
+//             group's query heads
+//   selected  the same over the head's index list: partial u_S and the four sums over S1 / S2; stage-1
+//             membership is read from the selection's stage-2 key array
+//   finish    one workgroup per query head: the 32 partials summed in double in a fixed order, the
 //             d_h x d matrix-vector product, the norm of the result and the closed forms
 #include "common.hpp"
 
 namespace ckv {
 
 constexpr int DG_THREADS = 256;
-constexpr int DG_CHUNK = 256;
+constexpr int DG_CHUNK = 256;  // == DG_THREADS: a thread stages one token of a chunk
+constexpr int DG_PARTS = 32;   // workgroups (and partial sums) per head
 constexpr int DG_GMAX = 8; // query heads of a group handled by one workgroup (more: blockIdx.z)
 constexpr uint32_t DG_TAKEN = 0xFFFFFFFFu; // the selection's mark for stage-1 entries in its stage-2 keys
 
@@ -31,9 +33,9 @@ struct DiagArgs {
     const int32_t *idx;   // [batch*Hkv, max_budget]
     const int32_t *count; // [batch*Hkv]
     const void *v;
-    float *part_all;      // [batch*H][n_chunks][dh + 2]: u_all, C, M
-    float *part_sel;      // [batch*H][n_chunks][dh + 4]: u_S, sigma, s2, D1, D2
-    int H, Hkv, G, dh, n, max_budget, n_chunks;
+    float *part_all;      // [batch*H][DG_PARTS][dh + 2]: u_all, C, M
+    float *part_sel;      // [batch*H][DG_PARTS][dh + 4]: u_S, sigma, s2, D1, D2
+    int H, Hkv, G, dh, n, max_budget;
     float a_scale;        // 1, or 1/W when the stored score is the window sum
     int64_t vs0, vs1, vs2;
 };
@@ -91,82 +93,74 @@ __device__ __forceinline__ void load8_f32(const float *p, float (&x)[8])
     x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
 }
 
-// SELECTED = false: tokens [chunk * 256, ...) of the head.  SELECTED = true: entries j of the index list.
+// SELECTED = false: the head's tokens.  SELECTED = true: the entries j of its index list.
+// Workgroup `part` of a head takes the 256-element chunks part, part + DG_PARTS, ... and writes one partial.
 template <typename T, bool SELECTED>
 __global__ __launch_bounds__(DG_THREADS) void diag_partial_kernel(DiagArgs A)
 {
     __shared__ float a_s[DG_GMAX][DG_CHUNK];   // A of the chunk's tokens, per query head of the group
-    __shared__ int tok_s[DG_CHUNK];            // SELECTED: token index (-1 = skip); stage-1 flag in st1_s
-    __shared__ unsigned char st1_s[DG_CHUNK];
+    __shared__ int tok_s[DG_CHUNK];            // token index (-1 = skip)
+    __shared__ unsigned char st1_s[DG_CHUNK];  // SELECTED: taken in stage 1
     __shared__ float red_s[DG_THREADS];
-    __shared__ float u_s[DG_THREADS * 8]; // [row lanes][dh]
+    __shared__ float u_s[DG_THREADS * 8];      // [row lanes][dh]
 
-    const int chunk = blockIdx.x, head = blockIdx.y; // head = bi * Hkv + g
+    const int part = blockIdx.x, head = blockIdx.y; // head = bi * Hkv + g
     const int bi = head / A.Hkv, g = head % A.Hkv;
     const int hh0 = blockIdx.z * DG_GMAX, gc = min(DG_GMAX, A.G - hh0);
     const int h0 = g * A.G + hh0;                                    // first query head handled here
     const int limit = SELECTED ? min(max(A.count[head], 0), A.max_budget) : A.n;
-    const int j0 = chunk * DG_CHUNK;
-    const int len = min(DG_CHUNK, limit - j0);
-    const bool empty = len <= 0; // uniform over the workgroup; partials of an empty chunk are written as zeros
+    const int chunks = (limit + DG_CHUNK - 1) / DG_CHUNK;
 
-    for (int jj = threadIdx.x; jj < DG_CHUNK; jj += DG_THREADS) {
-        int i = -1;
-        unsigned char st1 = 0;
-        if (jj < len) {
-            if (SELECTED) {
-                i = A.idx[(size_t)head * A.max_budget + j0 + jj];
-                if (i < 0 || i >= A.n) i = -1;
-                else st1 = A.keys2[(size_t)head * A.n + i] == DG_TAKEN;
-            } else {
-                i = j0 + jj;
-            }
-        }
-        tok_s[jj] = i;
-        st1_s[jj] = st1;
-        for (int hh = 0; hh < gc; ++hh)
-            a_s[hh][jj] = i >= 0 ? A.a_raw[((size_t)bi * A.H + h0 + hh) * A.n + i] * A.a_scale : 0.0f;
-    }
-    __syncthreads();
-
-    // scalar sums: thread-strided over the chunk, then reduced over the workgroup
-    for (int hh = 0; hh < gc; ++hh) {
-        const float *nrm = A.vnorm + ((size_t)bi * A.H + h0 + hh) * A.n;
-        float c0 = 0.0f, c1 = 0.0f, c2 = 0.0f, c3 = 0.0f, mn = INFINITY;
-        for (int jj = threadIdx.x; jj < DG_CHUNK; jj += DG_THREADS) {
-            const int i = tok_s[jj];
-            if (i < 0) continue;
-            const float a = a_s[hh][jj], N = nrm[i];
-            if (SELECTED) {
-                if (st1_s[jj]) { c0 += a; c2 += a * N; } else { c1 += a; c3 += a * N; }
-            } else {
-                c0 += a * N;
-                mn = fminf(mn, N);
-            }
-        }
-        float *dst = SELECTED ? A.part_sel + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 4) + A.dh
-                              : A.part_all + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 2) + A.dh;
-        c0 = block_sum_f32(c0, red_s);
-        if (SELECTED) {
-            c1 = block_sum_f32(c1, red_s);
-            c2 = block_sum_f32(c2, red_s);
-            c3 = block_sum_f32(c3, red_s);
-            if (threadIdx.x == 0) { dst[0] = c0; dst[1] = c1; dst[2] = c2; dst[3] = c3; }
-        } else {
-            mn = block_min_f32(mn, red_s);
-            if (threadIdx.x == 0) { dst[0] = c0; dst[1] = mn; }
-        }
-    }
-
-    // weighted value sums: thread = (row lane, group of 8 columns); one 16-byte (bf16) or 32-byte (f32) load per row
+    // thread = (row lane, group of 8 columns) for the value sums: one 16-byte (bf16) or 32-byte (f32) load per row
     const int groups = A.dh >> 3, cg = threadIdx.x % groups, lane = threadIdx.x / groups, lanes = DG_THREADS / groups;
+    const T *vb = reinterpret_cast<const T *>(A.v) + bi * A.vs0 + g * A.vs1 + cg * 8;
     float acc[DG_GMAX][8];
+    float sc[DG_GMAX][4]; // SELECTED: sigma, s2, D1, D2; else C, min N
 #pragma unroll
-    for (int hh = 0; hh < DG_GMAX; ++hh)
+    for (int hh = 0; hh < DG_GMAX; ++hh) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[hh][e] = 0.0f;
-    if (!empty) {
-        const T *vb = reinterpret_cast<const T *>(A.v) + bi * A.vs0 + g * A.vs1 + cg * 8;
+        sc[hh][0] = sc[hh][2] = sc[hh][3] = 0.0f;
+        sc[hh][1] = SELECTED ? 0.0f : INFINITY;
+    }
+
+    for (int chunk = part; chunk < chunks; chunk += DG_PARTS) { // uniform over the workgroup
+        const int j0 = chunk * DG_CHUNK;
+        const int len = min(DG_CHUNK, limit - j0);
+        __syncthreads(); // the previous chunk's staging is no longer read
+        {
+            const int jj = threadIdx.x; // DG_CHUNK == DG_THREADS
+            int i = -1;
+            unsigned char st1 = 0;
+            if (jj < len) {
+                if (SELECTED) {
+                    i = A.idx[(size_t)head * A.max_budget + j0 + jj];
+                    if (i < 0 || i >= A.n) i = -1;
+                    else st1 = A.keys2[(size_t)head * A.n + i] == DG_TAKEN;
+                } else {
+                    i = j0 + jj;
+                }
+            }
+            tok_s[jj] = i;
+            st1_s[jj] = st1;
+#pragma unroll
+            for (int hh = 0; hh < DG_GMAX; ++hh)
+                if (hh < gc) {
+                    const float a = i >= 0 ? A.a_raw[((size_t)bi * A.H + h0 + hh) * A.n + i] * A.a_scale : 0.0f;
+                    a_s[hh][jj] = a;
+                    // scalar sums: this thread's own token
+                    if (i >= 0) {
+                        const float N = A.vnorm[((size_t)bi * A.H + h0 + hh) * A.n + i];
+                        if (SELECTED) {
+                            if (st1) { sc[hh][0] += a; sc[hh][2] += a * N; } else { sc[hh][1] += a; sc[hh][3] += a * N; }
+                        } else {
+                            sc[hh][0] += a * N;
+                            sc[hh][1] = fminf(sc[hh][1], N);
+                        }
+                    }
+                }
+        }
+        __syncthreads();
 #pragma unroll 4
         for (int jj = lane; jj < len; jj += lanes) {
             const int i = tok_s[jj];
@@ -185,9 +179,23 @@ __global__ __launch_bounds__(DG_THREADS) void diag_partial_kernel(DiagArgs A)
                 }
         }
     }
+
+    // one partial per (query head, part): scalars, then the d_h value sums (row lanes merged through LDS)
 #pragma unroll
     for (int hh = 0; hh < DG_GMAX; ++hh) {
         if (hh < gc) { // uniform over the workgroup
+            const size_t slot = ((size_t)bi * A.H + h0 + hh) * DG_PARTS + part;
+            float *dst = SELECTED ? A.part_sel + slot * (A.dh + 4) : A.part_all + slot * (A.dh + 2);
+            const float c0 = block_sum_f32(sc[hh][0], red_s);
+            if (SELECTED) {
+                const float c1 = block_sum_f32(sc[hh][1], red_s);
+                const float c2 = block_sum_f32(sc[hh][2], red_s);
+                const float c3 = block_sum_f32(sc[hh][3], red_s);
+                if (threadIdx.x == 0) { dst[A.dh] = c0; dst[A.dh + 1] = c1; dst[A.dh + 2] = c2; dst[A.dh + 3] = c3; }
+            } else {
+                const float mn = block_min_f32(sc[hh][1], red_s);
+                if (threadIdx.x == 0) { dst[A.dh] = c0; dst[A.dh + 1] = mn; }
+            }
             __syncthreads();
 #pragma unroll
             for (int e = 0; e < 8; ++e) u_s[lane * A.dh + cg * 8 + e] = acc[hh][e];
@@ -195,8 +203,6 @@ __global__ __launch_bounds__(DG_THREADS) void diag_partial_kernel(DiagArgs A)
             if ((int)threadIdx.x < A.dh) {
                 float sum = 0.0f;
                 for (int l = 0; l < lanes; ++l) sum += u_s[l * A.dh + threadIdx.x];
-                float *dst = SELECTED ? A.part_sel + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 4)
-                                      : A.part_all + (((size_t)bi * A.H + h0 + hh) * A.n_chunks + chunk) * (A.dh + 2);
                 dst[threadIdx.x] = sum;
             }
         }
@@ -213,22 +219,21 @@ __global__ __launch_bounds__(DG_THREADS) void diag_finish_kernel(DiagArgs A, con
     const int bh = blockIdx.x; // bi * H + h
     const int bi = bh / A.H, h = bh % A.H, g = h / A.G;
     const int head = bi * A.Hkv + g;
-    const int cnt = min(max(A.count[head], 0), A.max_budget);
-    const int sel_chunks = (cnt + DG_CHUNK - 1) / DG_CHUNK;
-    const float *pa = A.part_all + (size_t)bh * A.n_chunks * (A.dh + 2);
-    const float *ps = A.part_sel + (size_t)bh * A.n_chunks * (A.dh + 4);
+    (void)head;
+    const float *pa = A.part_all + (size_t)bh * DG_PARTS * (A.dh + 2);
+    const float *ps = A.part_sel + (size_t)bh * DG_PARTS * (A.dh + 4);
 
     if (threadIdx.x < 6) {
-        // 0: C  1: M  2: sigma  3: s2  4: D1  5: D2 -- each summed over its chunks in ascending order
+        // 0: C  1: M  2: sigma  3: s2  4: D1  5: D2 -- each summed over the parts in ascending order
         const int q = threadIdx.x;
         double acc = q == 1 ? (double)INFINITY : 0.0;
         if (q < 2) {
-            for (int c = 0; c < A.n_chunks; ++c) {
+            for (int c = 0; c < DG_PARTS; ++c) {
                 const double x = (double)pa[(size_t)c * (A.dh + 2) + A.dh + q];
                 acc = q == 1 ? fmin(acc, x) : acc + x;
             }
         } else {
-            for (int c = 0; c < sel_chunks; ++c) acc += (double)ps[(size_t)c * (A.dh + 4) + A.dh + (q - 2)];
+            for (int c = 0; c < DG_PARTS; ++c) acc += (double)ps[(size_t)c * (A.dh + 4) + A.dh + (q - 2)];
         }
         scal_s[q] = acc;
     }
@@ -237,8 +242,8 @@ __global__ __launch_bounds__(DG_THREADS) void diag_finish_kernel(DiagArgs A, con
     const double s = sigma + s2;
     if ((int)threadIdx.x < A.dh) {
         double ua = 0.0, us = 0.0;
-        for (int c = 0; c < A.n_chunks; ++c) ua += (double)pa[(size_t)c * (A.dh + 2) + threadIdx.x];
-        for (int c = 0; c < sel_chunks; ++c) us += (double)ps[(size_t)c * (A.dh + 4) + threadIdx.x];
+        for (int c = 0; c < DG_PARTS; ++c) ua += (double)pa[(size_t)c * (A.dh + 2) + threadIdx.x];
+        for (int c = 0; c < DG_PARTS; ++c) us += (double)ps[(size_t)c * (A.dh + 4) + threadIdx.x];
         diff_s[threadIdx.x] = s > 0.0 ? ua - us / s : ua;
     }
     __syncthreads();
@@ -281,8 +286,7 @@ __global__ __launch_bounds__(DG_THREADS) void diag_finish_kernel(DiagArgs A, con
 
 size_t diagnostics_workspace_floats(const Dims &d)
 {
-    const size_t n_chunks = (size_t)(d.n + DG_CHUNK - 1) / DG_CHUNK;
-    return (size_t)d.batch * d.H * n_chunks * (2 * (size_t)d.dh + 6);
+    return (size_t)d.batch * d.H * DG_PARTS * (2 * (size_t)d.dh + 6);
 }
 
 hipError_t launch_diagnostics(const Dims &d, int dtype, int out_in, const void *v, const void *w_o, const float *a_raw,
@@ -292,21 +296,19 @@ hipError_t launch_diagnostics(const Dims &d, int dtype, int out_in, const void *
     DiagArgs A;
     A.a_raw = a_raw; A.vnorm = vnorm; A.keys2 = keys2; A.idx = idx; A.count = count; A.v = v;
     A.H = d.H; A.Hkv = d.Hkv; A.G = d.G; A.dh = d.dh; A.n = d.n; A.max_budget = max_budget;
-    A.n_chunks = (d.n + DG_CHUNK - 1) / DG_CHUNK;
     A.part_all = part;
-    A.part_sel = part + (size_t)d.batch * d.H * A.n_chunks * (d.dh + 2);
+    A.part_sel = part + (size_t)d.batch * d.H * DG_PARTS * (d.dh + 2);
     A.a_scale = d.window_sum ? 1.0f / (float)d.W : 1.0f;
     A.vs0 = d.vs[0]; A.vs1 = d.vs[1]; A.vs2 = d.vs[2];
     const int gz = (d.G + DG_GMAX - 1) / DG_GMAX;
-    const int sel_chunks = (max_budget + DG_CHUNK - 1) / DG_CHUNK;
     dim3 block(DG_THREADS);
     if (dtype == CKV_F32) {
-        hipLaunchKernelGGL((diag_partial_kernel<float, false>), dim3(A.n_chunks, d.batch * d.Hkv, gz), block, 0, s, A);
-        hipLaunchKernelGGL((diag_partial_kernel<float, true>), dim3(sel_chunks, d.batch * d.Hkv, gz), block, 0, s, A);
+        hipLaunchKernelGGL((diag_partial_kernel<float, false>), dim3(DG_PARTS, d.batch * d.Hkv, gz), block, 0, s, A);
+        hipLaunchKernelGGL((diag_partial_kernel<float, true>), dim3(DG_PARTS, d.batch * d.Hkv, gz), block, 0, s, A);
         hipLaunchKernelGGL(diag_finish_kernel<float>, dim3(d.batch * d.H), block, 0, s, A, w_o, d.dm, out_in, d.norm, out);
     } else {
-        hipLaunchKernelGGL((diag_partial_kernel<bf16_t, false>), dim3(A.n_chunks, d.batch * d.Hkv, gz), block, 0, s, A);
-        hipLaunchKernelGGL((diag_partial_kernel<bf16_t, true>), dim3(sel_chunks, d.batch * d.Hkv, gz), block, 0, s, A);
+        hipLaunchKernelGGL((diag_partial_kernel<bf16_t, false>), dim3(DG_PARTS, d.batch * d.Hkv, gz), block, 0, s, A);
+        hipLaunchKernelGGL((diag_partial_kernel<bf16_t, true>), dim3(DG_PARTS, d.batch * d.Hkv, gz), block, 0, s, A);
         hipLaunchKernelGGL(diag_finish_kernel<bf16_t>, dim3(d.batch * d.H), block, 0, s, A, w_o, d.dm, out_in, d.norm, out);
     }
     return hipGetLastError();
