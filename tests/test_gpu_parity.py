@@ -536,6 +536,36 @@ def test_diagnostics_special_budgets_and_baseline_selection(P):
     assert_diagnostics_close(got, ref, "attention-only selection")
 
 
+# ------------------------------------------------------------------------------------------------ odd shapes
+ODD_SHAPES = {
+    "g16_w40_dm128": dict(base="llama32k", n_q_heads=16, n_kv_heads=1, n_ctx=700, window=40, d_model=128, pool_kernel=1,
+                          budget=150),
+    "mha_w96_batch2": dict(base="llama32k", n_q_heads=3, n_kv_heads=3, n_ctx=300, window=96, d_model=256, batch=2, budget=120),
+    "g12_two_wave_groups": dict(base="llama32k", n_q_heads=24, n_kv_heads=2, n_ctx=400, window=8, d_model=128, budget=77),
+    "g7_w64": dict(base="llama32k", n_q_heads=28, n_kv_heads=4, n_ctx=1000, window=64, d_model=384, budget=333),
+    "f32_dh64_g3_w1_dm32": dict(base="tiny", n_q_heads=6, n_kv_heads=2, n_ctx=257, window=1, d_model=32, pool_kernel=3,
+                                budget=40),
+    "bf16_dh64_g2": dict(base="llama32k", n_q_heads=4, n_kv_heads=2, head_dim=64, n_ctx=515, window=16, d_model=96, budget=100),
+}
+
+
+@pytest.mark.parametrize("shape", sorted(ODD_SHAPES))
+def test_odd_shapes_every_entry_point(P, shape):
+    """Group sizes 1, 2, 3, 7, 12 and 16, windows 1 to 96, the smallest d_model, both dtypes and head sizes: whole pass,
+    allocation and diagnostics against the oracle."""
+    kw = dict(ODD_SHAPES[shape])
+    cfg = CONFIGS[kw.pop("base")].with_(**kw)
+    t = make_layer(cfg)
+    res, ref, _ = check_full(P, cfg, t, label=shape)
+    total = cfg.n_kv_heads * cfg.budget
+    got_b = run_allocate(P, res.attn, total, np.float32(0.3))
+    assert np.array_equal(got_b, O.allocate(res.attn.astype(np.float64), total, np.float32(0.3)))
+    got, idx, _ = run_diagnostics(P, cfg, t, cfg.budget, cfg.alpha)
+    ref_d, ref_idx = oracle_diagnostics(cfg, t, cfg.budget, cfg.alpha)
+    assert np.array_equal(idx, ref_idx)
+    assert_diagnostics_close(got, ref_d, shape)
+
+
 # ------------------------------------------------------------------------------------------------ full-size
 def _full_size_check(P, cfg, t, sweeps=None, layer_label=""):
     """Full BASELINE shape in the launch configuration the benchmark times (output-major W_O).
