@@ -82,7 +82,7 @@ def test_batch_and_head_dim_64(P):
     check_full(P, cfg32, t, wo_out_in=False, label="b3 dh64 f32")
 
 
-@pytest.mark.parametrize("case", ["llama_gram", "llama_valu", "qwen_gram", "tiny_f32", "dh64_bf16"])
+@pytest.mark.parametrize("case", ["llama_gram", "llama_valu", "qwen_gram", "tiny_f32", "dh64_bf16", "g16_gram", "mha_batch2_gram"])
 def test_l2_norm_variant(P, case):
     """L2 distance variant: N = ||v W_O^h||_2.  The bf16 d_h = 128 path goes through the Gram matrix
     (exact for the 2-norm); the oracle evaluates the definition (all d_model products) in float64."""
@@ -96,6 +96,10 @@ def test_l2_norm_variant(P, case):
         cfg = reduced(CONFIGS["qwen128k"], 3000, d_model=2560)
     elif case == "tiny_f32":
         cfg, wo = CONFIGS["tiny"], False
+    elif case == "g16_gram":
+        cfg = reduced(CONFIGS["llama32k"], 2100, d_model=512, n_q_heads=16, n_kv_heads=1)
+    elif case == "mha_batch2_gram":
+        cfg = reduced(CONFIGS["llama32k"], 1300, d_model=512, n_q_heads=3, n_kv_heads=3, batch=2)
     else:
         cfg = reduced(CONFIGS["llama32k"], 700, d_model=256, head_dim=64, n_q_heads=6, n_kv_heads=3, window=5)
     t = make_layer(cfg)
@@ -630,6 +634,34 @@ def test_full_size_diagnostics_one_kv_group_llama32k(P):
     assert np.all(got[..., f["L"]] <= got[..., f["theta"]]) and np.all(got[..., f["theta"]] <= got[..., f["theta_hat"]] * (1 + 1e-5))
     print(f"[llama32k full] heads with sigma > 0.5: {(got[..., f['sigma']] > 0.5).mean():.3f}; mean L {got[..., f['L']].mean():.4f} "
           f"theta_hat {got[..., f['theta_hat']].mean():.4f} theta_relax {got[..., f['theta_relax']].mean():.4f}")
+
+
+@pytest.mark.parametrize("name", ["llama32k", "llama128k"])
+def test_full_size_l2_with_prepared_gram(P, name):
+    """The launch configuration `bench.py --norm l2` times (several row tiles per workgroup): magnitudes on sampled
+    tokens against the oracle's definition, selection exact on the GPU's own keys."""
+    import torch
+    cfg = CONFIGS[name]
+    t = make_layer(cfg)
+    prep = cfg_desc(P, cfg, flags=P.CKV_WO_OUT_IN, norm=P.CKV_NORM_L2)
+    dev = to_device(cfg, t, True)
+    ws = torch.empty(P.workspace_bytes(prep, cfg.budget), dtype=torch.uint8, device="cuda")
+    gram = torch.empty(P.gram_bytes(prep), dtype=torch.uint8, device="cuda")
+    P.criticalkv_prepare_gram(prep, dev["w_o"], gram, workspace=ws)
+    dev["w_o"] = gram
+    del ws
+    res = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, flags=P.CKV_WO_IS_GRAM, norm=P.CKV_NORM_L2, dev=dev)
+    r = np.random.Generator(np.random.PCG64(321))
+    rows = np.unique(np.concatenate([r.integers(0, cfg.n_ctx, 256), [0, 1, 511, 512, 4095, 4096, cfg.n_ctx - 2, cfg.n_ctx - 1]]))
+    N_s = O.projected_value_norm(t["v"][:, :, rows], t["w_o"], cfg.n_q_heads, norm=2)
+    e_v = assert_scores_close(res.vnorm[:, :, rows], N_s, "vnorm L2 (sampled tokens)")
+    ref_idx, ref_count, _ = O.select(res.attn.astype(np.float64), res.crit.astype(np.float64), cfg.budget, np.float32(cfg.alpha))
+    assert np.array_equal(res.count, ref_count) and np.array_equal(res.idx, ref_idx)
+    assert_compaction_exact(res, t, cfg.budget)
+    assert np.isfinite(res.vnorm).all() and (res.vnorm > 0).all()
+    print(f"[{name} L2 full] max rel err vnorm {e_v[0]:.2e} on {rows.size} sampled tokens")
+    del res, dev
+    torch.cuda.empty_cache()
 
 
 def test_full_size_llama128k(P):
