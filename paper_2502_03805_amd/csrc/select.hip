@@ -13,9 +13,9 @@
 //   zero      clear the digit histograms
 //   hist 1.0  digit-0 histogram of attn            (LDS histogram per slice, flushed with integer atomics)
 //   hist 1.1  find digit 0, digit-1 histogram of the entries that match it
-//   hist 1.2  find digit 1, digit-2 histogram
-//   ties 1    find digit 2 -> tau1, r1; ties per slice
-//   mark      stage-1 membership (ties ranked through the per-slice counts), stage-2 keys written
+//   hist 1.2  find digit 1, digit-2 histogram (each slice also keeps its own copy)
+//   mark      find digit 2 -> tau1, r1; stage-1 membership (ties ranked through the slices' own digit-2
+//             histograms: the ties of a slice are its count at digit 2 of tau1), stage-2 keys written
 //             (stage-1 entries carry a reserved key), digit-0 histogram of stage 2
 //   hist 2.1, hist 2.2, then
 //   count     tau2, r2; per slice: selected entries and ties
@@ -43,7 +43,8 @@ struct SelArgs {
     uint32_t *keys2;   // [heads][n]
     uint32_t *hist;    // [heads][2 stages][3 passes][SEL_BINS]
     uint32_t *state;   // [heads][2 stages][ST_WORDS]
-    uint32_t *slices;  // [heads][3][n_slices]: ties of stage 1, selected (non-tie) count, ties of stage 2
+    uint32_t *slices;  // [heads][3][n_slices]: (unused), selected (non-tie) count, ties of stage 2
+    uint32_t *slice_hist; // [heads][n_slices][1024]: each slice's digit-2 histogram of stage 1
     int32_t *idx;
     int32_t *count;
     double alpha;
@@ -209,21 +210,23 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelArgs A)
         const uint32_t c = sh.hist[b];
         if (c) atomicAdd(&dst[b], c);
     }
+    if (STAGE == 0 && PASS == 2) { // the slice's own counts: the mark kernel reads its ties from here
+        uint32_t *mine = A.slice_hist + ((size_t)head * A.n_slices + slice) * 1024;
+        for (int b = threadIdx.x; b < 1024; b += SEL_THREADS) mine[b] = sh.hist[b];
+    }
 }
 
-// Decodes the last digit of a stage (tau, r) and counts, per slice, what the ordered passes need.
-//   STAGE 0: ties of stage 1 (key == tau1).
-//   STAGE 1: selected entries without ties (stage-1 members and keys > tau2) and ties of stage 2.
-template <int STAGE>
+// Decodes the last digit of stage 2 (tau2, r2) and counts, per slice, what the ordered write needs:
+// selected entries without ties (stage-1 members and keys > tau2) and ties of stage 2.
 __global__ __launch_bounds__(SEL_THREADS) void select_count_kernel(SelArgs A)
 {
     __shared__ SelShared sh;
     const int slice = blockIdx.x, head = blockIdx.y;
     int B, b1, b2;
     head_budget(A, head, B, b1, b2);
-    const uint32_t want = STAGE == 0 ? (uint32_t)b1 : (uint32_t)b2;
-    uint32_t *hist = A.hist + ((size_t)head * 2 + STAGE) * 3 * SEL_BINS;
-    uint32_t *st = A.state + ((size_t)head * 2 + STAGE) * ST_WORDS;
+    const uint32_t want = (uint32_t)b2;
+    uint32_t *hist = A.hist + ((size_t)head * 2 + 1) * 3 * SEL_BINS;
+    uint32_t *st = A.state + ((size_t)head * 2 + 1) * ST_WORDS;
     uint32_t tau = 0u, r = 0u;
     if (want) {
         const uint32_t d0 = st[ST_D0], a0 = st[ST_A0], d1 = st[ST_D1], a1 = st[ST_A1];
@@ -234,7 +237,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_count_kernel(SelArgs A)
     }
     if (slice == 0 && threadIdx.x == 0) { st[ST_TAU] = tau; st[ST_R] = r; }
 
-    const uint32_t *src = (STAGE == 0 ? A.attn : A.keys2) + (size_t)head * A.n;
+    const uint32_t *src = A.keys2 + (size_t)head * A.n;
     const bool vec_ok = (A.n & 3) == 0;
     const int i0 = slice * SEL_SLICE + threadIdx.x * SEL_PER_THREAD;
     uint32_t w[8];
@@ -242,24 +245,16 @@ __global__ __launch_bounds__(SEL_THREADS) void select_count_kernel(SelArgs A)
     uint32_t n_tie = 0u, n_sel = 0u;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const uint32_t key = STAGE == 0 ? order_key(w[j]) : w[j];
+        const uint32_t key = w[j];
         const bool valid = i0 + j < A.n;
-        if (STAGE == 0) {
-            n_tie += (want && valid && key == tau) ? 1u : 0u;
-        } else {
-            const bool taken = valid && key == SEL_TAKEN;
-            n_sel += (taken || (want && valid && key > tau)) ? 1u : 0u;
-            n_tie += (want && valid && key == tau) ? 1u : 0u; // tau is a finite float's image, never SEL_TAKEN
-        }
+        const bool taken = valid && key == SEL_TAKEN;
+        n_sel += (taken || (want && valid && key > tau)) ? 1u : 0u;
+        n_tie += (want && valid && key == tau) ? 1u : 0u; // tau is a finite float's image, never SEL_TAKEN
     }
     uint32_t *sl = A.slices + (size_t)head * 3 * A.n_slices;
     const uint32_t ties = block_sum(sh, n_tie);
-    if (STAGE == 0) {
-        if (threadIdx.x == 0) sl[slice] = ties;
-    } else {
-        const uint32_t sel = block_sum(sh, n_sel);
-        if (threadIdx.x == 0) { sl[A.n_slices + slice] = sel; sl[2 * A.n_slices + slice] = ties; }
-    }
+    const uint32_t sel = block_sum(sh, n_sel);
+    if (threadIdx.x == 0) { sl[A.n_slices + slice] = sel; sl[2 * A.n_slices + slice] = ties; }
 }
 
 // Stage-1 membership, stage-2 keys, digit-0 histogram of stage 2.
@@ -269,13 +264,22 @@ __global__ __launch_bounds__(SEL_THREADS) void select_mark_kernel(SelArgs A)
     const int slice = blockIdx.x, head = blockIdx.y;
     int B, b1, b2;
     head_budget(A, head, B, b1, b2);
-    const uint32_t *st1 = A.state + ((size_t)head * 2 + 0) * ST_WORDS;
-    const uint32_t tau1 = st1[ST_TAU], r1 = st1[ST_R];
-    const uint32_t *sl = A.slices + (size_t)head * 3 * A.n_slices;
-    // ties of stage 1 in earlier slices
-    uint32_t before = 0u;
-    for (int s = threadIdx.x; s < slice; s += SEL_THREADS) before += sl[s];
-    before = block_sum(sh, before);
+    uint32_t *st1 = A.state + ((size_t)head * 2 + 0) * ST_WORDS;
+    uint32_t tau1 = 0u, r1 = 0u, before = 0u;
+    if (b1 > 0) { // uniform over the workgroup
+        // last digit of the stage-1 threshold, decided redundantly by every workgroup
+        const uint32_t d0 = st1[ST_D0], a0 = st1[ST_A0], d1 = st1[ST_D1], a1 = st1[ST_A1];
+        uint32_t d2, a2;
+        find_digit(sh, A.hist + ((size_t)head * 2 + 0) * 3 * SEL_BINS + 2 * SEL_BINS, 1024, (uint32_t)b1 - a0 - a1, d2, a2);
+        tau1 = (d0 << DSHIFT0) | (d1 << DSHIFT1) | d2;
+        r1 = (uint32_t)b1 - a0 - a1 - a2;
+        if (slice == 0 && threadIdx.x == 0) { st1[ST_TAU] = tau1; st1[ST_R] = r1; }
+        // ties of stage 1 in earlier slices: their counts at digit d2 (only entries with the threshold's first two
+        // digits were counted there)
+        const uint32_t *sh2 = A.slice_hist + (size_t)head * A.n_slices * 1024 + d2;
+        for (int s = threadIdx.x; s < slice; s += SEL_THREADS) before += sh2[(size_t)s * 1024];
+        before = block_sum(sh, before);
+    }
 
     const bool vec_ok = (A.n & 3) == 0;
     const int i0 = slice * SEL_SLICE + threadIdx.x * SEL_PER_THREAD;
@@ -397,7 +401,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_write_kernel(SelArgs A)
 size_t select_workspace_words(int heads, int n)
 {
     const size_t n_slices = (size_t)(n + SEL_SLICE - 1) / SEL_SLICE;
-    return (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS) + (size_t)heads * 3 * n_slices;
+    return (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS) + (size_t)heads * 3 * n_slices + (size_t)heads * n_slices * 1024;
 }
 
 // heads rows of n keys each (a row is one (batch item, kv head), or one whole batch item for the allocation)
@@ -417,17 +421,17 @@ hipError_t launch_select_rows(int heads, int n, const float *attn, const float *
     A.alpha = (double)alpha;
     A.n = n; A.max_budget = max_budget;
     A.n_slices = (n + SEL_SLICE - 1) / SEL_SLICE;
+    A.slice_hist = A.slices + (size_t)heads * 3 * A.n_slices;
     const size_t zero_words = (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS);
     dim3 grid(A.n_slices, heads), block(SEL_THREADS);
     hipLaunchKernelGGL(select_zero_kernel, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, s, scratch, zero_words);
     hipLaunchKernelGGL((select_hist_kernel<0, 0>), grid, block, 0, s, A);
     hipLaunchKernelGGL((select_hist_kernel<0, 1>), grid, block, 0, s, A);
     hipLaunchKernelGGL((select_hist_kernel<0, 2>), grid, block, 0, s, A);
-    hipLaunchKernelGGL(select_count_kernel<0>, grid, block, 0, s, A);
     hipLaunchKernelGGL(select_mark_kernel, grid, block, 0, s, A);
     hipLaunchKernelGGL((select_hist_kernel<1, 1>), grid, block, 0, s, A);
     hipLaunchKernelGGL((select_hist_kernel<1, 2>), grid, block, 0, s, A);
-    hipLaunchKernelGGL(select_count_kernel<1>, grid, block, 0, s, A);
+    hipLaunchKernelGGL(select_count_kernel, grid, block, 0, s, A);
     hipLaunchKernelGGL(select_write_kernel, grid, block, 0, s, A);
     return hipGetLastError();
 }
