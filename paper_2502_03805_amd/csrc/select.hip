@@ -17,9 +17,10 @@
 //   mark      find digit 2 -> tau1, r1; stage-1 membership (ties ranked through the slices' own digit-2
 //             histograms: the ties of a slice are its count at digit 2 of tau1), stage-2 keys written
 //             (stage-1 entries carry a reserved key), digit-0 histogram of stage 2
-//   hist 2.1, hist 2.2, then
-//   count     tau2, r2; per slice: selected entries and ties
-//   write     ordered write of S1 u S2 from the per-slice counts; -1 tail; count
+//   hist 2.1, hist 2.2  (each slice also counts its entries above the digit just decided; 2.2 keeps the slice's
+//             digit-2 counts as suffix sums)
+//   write     find digit 2 -> tau2, r2; ordered write of S1 u S2: what earlier slices contribute is read from
+//             their per-slice counts; -1 tail; count
 // Every decision is integer arithmetic on exact counts, so the result does not depend on scheduling.
 #include "common.hpp"
 
@@ -43,7 +44,8 @@ struct SelArgs {
     uint32_t *keys2;   // [heads][n]
     uint32_t *hist;    // [heads][2 stages][3 passes][SEL_BINS]
     uint32_t *state;   // [heads][2 stages][ST_WORDS]
-    uint32_t *slices;  // [heads][3][n_slices]: (unused), selected (non-tie) count, ties of stage 2
+    uint32_t *slices;  // [heads][3][n_slices]: stage-1 members; stage-2 entries above the threshold at digit 0; at digit 1
+    uint32_t *slice_suf; // [heads][n_slices][1025]: each slice's digit-2 suffix counts of stage 2
     uint32_t *slice_hist; // [heads][n_slices][1024]: each slice's digit-2 histogram of stage 1
     int32_t *idx;
     int32_t *count;
@@ -189,11 +191,19 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelArgs A)
     uint32_t w[8];
     load8(src, i0, A.n, vec_ok, w);
     // runs of equal digits inside a thread's 8 tokens are merged into one atomic
-    uint32_t run_digit = 0u, run_len = 0u;
+    uint32_t run_digit = 0u, run_len = 0u, n_above = 0u;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const uint32_t key = STAGE == 0 ? order_key(w[j]) : w[j];
         const bool on = (i0 + j < A.n) && key != SEL_TAKEN && (key & pmask) == prefix;
+        if (STAGE == 1 && PASS >= 1) {
+            // stage 2: entries that beat the threshold at the digit this kernel has just decided (and agree with it
+            // on the digit before): the ordered write adds these per-slice counts up instead of counting again
+            constexpr uint32_t M0 = DMASK0 << DSHIFT0;
+            const bool above = (i0 + j < A.n) && key != SEL_TAKEN && (key & pmask) > prefix &&
+                               (PASS == 1 || (key & M0) == (prefix & M0));
+            n_above += above ? 1u : 0u;
+        }
         const uint32_t d = (key >> shift) & mask;
         if (on && run_len && d == run_digit) {
             ++run_len;
@@ -214,47 +224,25 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelArgs A)
         uint32_t *mine = A.slice_hist + ((size_t)head * A.n_slices + slice) * 1024;
         for (int b = threadIdx.x; b < 1024; b += SEL_THREADS) mine[b] = sh.hist[b];
     }
-}
-
-// Decodes the last digit of stage 2 (tau2, r2) and counts, per slice, what the ordered write needs:
-// selected entries without ties (stage-1 members and keys > tau2) and ties of stage 2.
-__global__ __launch_bounds__(SEL_THREADS) void select_count_kernel(SelArgs A)
-{
-    __shared__ SelShared sh;
-    const int slice = blockIdx.x, head = blockIdx.y;
-    int B, b1, b2;
-    head_budget(A, head, B, b1, b2);
-    const uint32_t want = (uint32_t)b2;
-    uint32_t *hist = A.hist + ((size_t)head * 2 + 1) * 3 * SEL_BINS;
-    uint32_t *st = A.state + ((size_t)head * 2 + 1) * ST_WORDS;
-    uint32_t tau = 0u, r = 0u;
-    if (want) {
-        const uint32_t d0 = st[ST_D0], a0 = st[ST_A0], d1 = st[ST_D1], a1 = st[ST_A1];
-        uint32_t d2, a2;
-        find_digit(sh, hist + 2 * SEL_BINS, 1024, want - a0 - a1, d2, a2);
-        tau = (d0 << DSHIFT0) | (d1 << DSHIFT1) | d2;
-        r = want - a0 - a1 - a2;
+    if (STAGE == 1 && PASS >= 1) {
+        uint32_t *sl = A.slices + (size_t)head * 3 * A.n_slices;
+        const uint32_t tot = block_sum(sh, n_above);
+        if (threadIdx.x == 0) sl[PASS * A.n_slices + slice] = tot;
     }
-    if (slice == 0 && threadIdx.x == 0) { st[ST_TAU] = tau; st[ST_R] = r; }
-
-    const uint32_t *src = A.keys2 + (size_t)head * A.n;
-    const bool vec_ok = (A.n & 3) == 0;
-    const int i0 = slice * SEL_SLICE + threadIdx.x * SEL_PER_THREAD;
-    uint32_t w[8];
-    load8(src, i0, A.n, vec_ok, w);
-    uint32_t n_tie = 0u, n_sel = 0u;
+    if (STAGE == 1 && PASS == 2) {
+        // the slice's digit-2 counts as suffix sums: suf[b] = entries of the slice (with the threshold's first two
+        // digits) whose digit 2 is >= b; suf[1024] = 0.  The write kernel reads suf[d2 + 1] and suf[d2].
+        static_assert(SEL_THREADS * 4 == 1024, "four bins per thread");
+        uint32_t h[4], local = 0u;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t key = w[j];
-        const bool valid = i0 + j < A.n;
-        const bool taken = valid && key == SEL_TAKEN;
-        n_sel += (taken || (want && valid && key > tau)) ? 1u : 0u;
-        n_tie += (want && valid && key == tau) ? 1u : 0u; // tau is a finite float's image, never SEL_TAKEN
+        for (int j = 0; j < 4; ++j) { h[j] = sh.hist[threadIdx.x * 4 + j]; local += h[j]; }
+        uint32_t total;
+        uint32_t below = block_exclusive_scan(sh, local, total); // entries in bins before this thread's
+        uint32_t *suf = A.slice_suf + ((size_t)head * A.n_slices + slice) * 1025;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { suf[threadIdx.x * 4 + j] = total - below; below += h[j]; }
+        if (threadIdx.x == 0) suf[1024] = 0u;
     }
-    uint32_t *sl = A.slices + (size_t)head * 3 * A.n_slices;
-    const uint32_t ties = block_sum(sh, n_tie);
-    const uint32_t sel = block_sum(sh, n_sel);
-    if (threadIdx.x == 0) { sl[A.n_slices + slice] = sel; sl[2 * A.n_slices + slice] = ties; }
 }
 
 // Stage-1 membership, stage-2 keys, digit-0 histogram of stage 2.
@@ -301,11 +289,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_mark_kernel(SelArgs A)
     for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS) sh.hist[b] = 0u;
     __syncthreads();
     uint32_t key2[8];
-    uint32_t run_digit = 0u, run_len = 0u;
+    uint32_t run_digit = 0u, run_len = 0u, n_taken = 0u;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         bool taken = gt[j];
         if (tie[j]) { taken = rank < r1; ++rank; }
+        n_taken += taken ? 1u : 0u;
         key2[j] = taken ? SEL_TAKEN : order_key(c[j]);
         const bool on = b2 > 0 && (i0 + j < A.n) && !taken;
         const uint32_t d = (key2[j] >> DSHIFT0) & DMASK0;
@@ -335,6 +324,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_mark_kernel(SelArgs A)
             if (cnt) atomicAdd(&dst[b], cnt);
         }
     }
+    const uint32_t taken_here = block_sum(sh, n_taken);
+    if (threadIdx.x == 0) A.slices[(size_t)head * 3 * A.n_slices + slice] = taken_here;
 }
 
 // Ordered write of S1 u S2.
@@ -344,20 +335,38 @@ __global__ __launch_bounds__(SEL_THREADS) void select_write_kernel(SelArgs A)
     const int slice = blockIdx.x, head = blockIdx.y;
     int B, b1, b2;
     head_budget(A, head, B, b1, b2);
-    const uint32_t *st2 = A.state + ((size_t)head * 2 + 1) * ST_WORDS;
-    const uint32_t tau2 = st2[ST_TAU], r2 = st2[ST_R];
-    const uint32_t *sel_cnt = A.slices + (size_t)head * 3 * A.n_slices + A.n_slices;
-    const uint32_t *tie_cnt = sel_cnt + A.n_slices;
-    // entries written and stage-2 ties seen by earlier slices: slice s' contributes
-    // sel_cnt[s'] + clamp(r2 - ties before s', 0, tie_cnt[s'])
+    uint32_t *st2 = A.state + ((size_t)head * 2 + 1) * ST_WORDS;
+    uint32_t tau2 = 0u, r2 = 0u, d2 = 0u;
+    if (b2 > 0) { // uniform over the workgroup: last digit of the stage-2 threshold
+        const uint32_t d0 = st2[ST_D0], a0 = st2[ST_A0], d1 = st2[ST_D1], a1 = st2[ST_A1];
+        uint32_t a2;
+        find_digit(sh, A.hist + ((size_t)head * 2 + 1) * 3 * SEL_BINS + 2 * SEL_BINS, 1024, (uint32_t)b2 - a0 - a1, d2, a2);
+        tau2 = (d0 << DSHIFT0) | (d1 << DSHIFT1) | d2;
+        r2 = (uint32_t)b2 - a0 - a1 - a2;
+        if (slice == 0 && threadIdx.x == 0) { st2[ST_TAU] = tau2; st2[ST_R] = r2; }
+    }
+    const uint32_t *taken_cnt = A.slices + (size_t)head * 3 * A.n_slices;
+    const uint32_t *above0 = taken_cnt + A.n_slices, *above1 = above0 + A.n_slices;
+    const uint32_t *suf = A.slice_suf + (size_t)head * A.n_slices * 1025;
+    // entries written and stage-2 ties seen by earlier slices: slice s' contributes its stage-1 members, its
+    // stage-2 keys above tau2 (counted digit by digit by the histogram kernels) and
+    // clamp(r2 - ties before s', 0, ties of s')
     uint32_t out_base = 0u, tie_base = 0u, carry = 0u;
     for (int c0 = 0; c0 < slice; c0 += SEL_THREADS) {
         const int s = c0 + threadIdx.x;
-        const uint32_t t = s < slice ? tie_cnt[s] : 0u;
+        uint32_t t = 0u, sel_s = 0u;
+        if (s < slice) {
+            sel_s = taken_cnt[s];
+            if (b2 > 0) {
+                const uint32_t ge = suf[(size_t)s * 1025 + d2], gt2 = suf[(size_t)s * 1025 + d2 + 1];
+                t = ge - gt2;
+                sel_s += above0[s] + above1[s] + gt2;
+            }
+        }
         uint32_t tot;
         const uint32_t tb = carry + block_exclusive_scan(sh, t, tot);
         uint32_t mine = 0u;
-        if (s < slice) mine = sel_cnt[s] + min(r2 > tb ? r2 - tb : 0u, t);
+        if (s < slice) mine = sel_s + min(r2 > tb ? r2 - tb : 0u, t);
         out_base += block_sum(sh, mine);
         carry += tot;
     }
@@ -401,7 +410,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_write_kernel(SelArgs A)
 size_t select_workspace_words(int heads, int n)
 {
     const size_t n_slices = (size_t)(n + SEL_SLICE - 1) / SEL_SLICE;
-    return (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS) + (size_t)heads * 3 * n_slices + (size_t)heads * n_slices * 1024;
+    return (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS) + (size_t)heads * 3 * n_slices + (size_t)heads * n_slices * (1024 + 1025);
 }
 
 // heads rows of n keys each (a row is one (batch item, kv head), or one whole batch item for the allocation)
@@ -422,6 +431,7 @@ hipError_t launch_select_rows(int heads, int n, const float *attn, const float *
     A.n = n; A.max_budget = max_budget;
     A.n_slices = (n + SEL_SLICE - 1) / SEL_SLICE;
     A.slice_hist = A.slices + (size_t)heads * 3 * A.n_slices;
+    A.slice_suf = A.slice_hist + (size_t)heads * A.n_slices * 1024;
     const size_t zero_words = (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS);
     dim3 grid(A.n_slices, heads), block(SEL_THREADS);
     hipLaunchKernelGGL(select_zero_kernel, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, s, scratch, zero_words);
@@ -431,7 +441,6 @@ hipError_t launch_select_rows(int heads, int n, const float *attn, const float *
     hipLaunchKernelGGL(select_mark_kernel, grid, block, 0, s, A);
     hipLaunchKernelGGL((select_hist_kernel<1, 1>), grid, block, 0, s, A);
     hipLaunchKernelGGL((select_hist_kernel<1, 2>), grid, block, 0, s, A);
-    hipLaunchKernelGGL(select_count_kernel, grid, block, 0, s, A);
     hipLaunchKernelGGL(select_write_kernel, grid, block, 0, s, A);
     return hipGetLastError();
 }
