@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per launch of the projection kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00 after calibration against a 1 GiB device copy); the runs and the
 # calibration are written up in profiles/whole_pass_llama_hbm_counters.md.  None where not measured.
-VPROJ_TRAFFIC_BYTES = {"llama32k": int(360.6 * 2**20), "llama128k": int(1332.7 * 2**20)}
+VPROJ_TRAFFIC_BYTES = {"llama32k": int(190.0 * 2**20), "llama128k": int(607.3 * 2**20)}
 
 
 class HipEvents:
