@@ -546,6 +546,10 @@ ODD_SHAPES = {
                           budget=150),
     "mha_w96_batch2": dict(base="llama32k", n_q_heads=3, n_kv_heads=3, n_ctx=300, window=96, d_model=256, batch=2, budget=120),
     "g12_two_wave_groups": dict(base="llama32k", n_q_heads=24, n_kv_heads=2, n_ctx=400, window=8, d_model=128, budget=77),
+    "n_equals_window_bf16": dict(base="llama32k", n_q_heads=8, n_kv_heads=2, n_ctx=32, window=32, d_model=128, budget=9, pool_kernel=3),
+    "single_entry_bf16": dict(base="llama32k", n_q_heads=4, n_kv_heads=2, n_ctx=1, window=1, d_model=128, budget=1, pool_kernel=1),
+    "single_entry_f32": dict(base="tiny", n_q_heads=2, n_kv_heads=2, n_ctx=1, window=1, d_model=32, budget=1, pool_kernel=1),
+    "n_equals_window_f32": dict(base="tiny", n_q_heads=4, n_kv_heads=2, n_ctx=5, window=5, d_model=64, budget=2, pool_kernel=5),
     "g7_w64": dict(base="llama32k", n_q_heads=28, n_kv_heads=4, n_ctx=1000, window=64, d_model=384, budget=333),
     "f32_dh64_g3_w1_dm32": dict(base="tiny", n_q_heads=6, n_kv_heads=2, n_ctx=257, window=1, d_model=32, pool_kernel=3,
                                 budget=40),
