@@ -297,6 +297,16 @@ def main():
                  + 2 * 4.0 * b * Hkv * n         # and read by the selection
                  + 2.0 * kv_bytes * B / n)       # kept rows read and written
     t_bound_ms = (flops / (PEAK_BF16_TFLOPS * 1e12) + hbm_bytes / (PEAK_HBM_GBS * 1e9)) * 1e3
+    # every stage against its own bound, from the medians of the stage breakdown: the two attention sweeps and the
+    # gather against HBM (algorithmic bytes at 8 TB/s), the projection against the bf16 MFMA peak
+    k_bytes = kv_bytes / 2 + b * H * cfg.window * dh * esize
+    stage_frac = {
+        "attn_stats_hbm": round(k_bytes / (PEAK_HBM_GBS * 1e9) / (stage_ms["attn_stats"] * 1e-3), 4),
+        "attn_colsum_hbm": round((k_bytes + 4.0 * b * H * n) / (PEAK_HBM_GBS * 1e9) / (stage_ms["attn_colsum"] * 1e-3), 4),
+        "compact_hbm": round(2.0 * kv_bytes * B / n / (PEAK_HBM_GBS * 1e9) / (stage_ms["compact"] * 1e-3), 4),
+    }
+    if flops:
+        stage_frac["vproj_mfma"] = round(flops / (PEAK_BF16_TFLOPS * 1e12) / (stage_ms["vproj"] * 1e-3), 4)
     if args.norm == "none":
         # two sweeps over K (stats, then window-reduced weights), each reading K and the window queries once
         sweep_bytes = 2.0 * (kv_bytes / 2 + b * H * cfg.window * dh * esize) + 2 * 4.0 * b * H * n
@@ -324,7 +334,7 @@ def main():
                    **({"layers": cfg.n_layers, "total_ms_all_layers": round(cfg.n_layers * ms_per_step, 3)}
                       if cfg.n_layers > 1 else {})},
         "roofline": roofline,
-        "stages_ms": stage_ms, "beside_the_pass_ms": extras_ms,
+        "stages_ms": stage_ms, "stages_frac_of_own_bound": stage_frac, "beside_the_pass_ms": extras_ms,
         "pass_lower_bound_ms": round(t_bound_ms, 4), "pass_frac_of_bound": round(t_bound_ms / ms_per_step, 4),
     }
 

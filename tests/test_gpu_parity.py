@@ -679,7 +679,7 @@ def test_full_size_qwen128k_with_budget_and_alpha_sweep(P):
     _full_size_check(P, cfg, make_layer(cfg), sweeps=sweeps)
 
 
-@pytest.mark.parametrize("layer", [0, 31])
+@pytest.mark.parametrize("layer", [0, 15, 31])
 def test_full_size_mistral_prefill_layer(P, layer):
     """One layer of the 32-layer batch-4 prefill workload (independent seeds per layer)."""
     cfg = CONFIGS["mistral_prefill"]
