@@ -18,7 +18,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
@@ -91,7 +90,7 @@ def main():
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     import paper_2502_03805_amd as P
-    from helpers import cfg_desc, to_device
+    from paper_2502_03805_amd.marshal import cfg_desc, to_device
     from workload import CONFIGS, make_layer
 
     P.load()
@@ -103,7 +102,7 @@ def main():
     nsets = args.sets or max(2, min(4, int(np.ceil(512e6 / kv_bytes))))
     l2 = args.norm == "l2"
     flags = P.CKV_WO_IS_GRAM if l2 else (P.CKV_ATTN_ONLY if args.norm == "none" else P.CKV_WO_OUT_IN)
-    desc = cfg_desc(P, cfg, flags=flags, norm=P.CKV_NORM_L2 if l2 else P.CKV_NORM_L1)
+    desc = cfg_desc(cfg, flags=flags, norm=P.CKV_NORM_L2 if l2 else P.CKV_NORM_L1)
     B = cfg.budget
     sets = []
     host0 = None
@@ -118,7 +117,7 @@ def main():
         sets.append(dev)
     if l2:
         # the Gram matrices depend on the pretrained projection only: prepared once, outside the timed steps
-        prep = cfg_desc(P, cfg, flags=P.CKV_WO_OUT_IN, norm=P.CKV_NORM_L2)
+        prep = cfg_desc(cfg, flags=P.CKV_WO_OUT_IN, norm=P.CKV_NORM_L2)
         gram = torch.empty(P.gram_bytes(prep), dtype=torch.uint8, device="cuda")
         ws0 = torch.empty(P.workspace_bytes(prep, B), dtype=torch.uint8, device="cuda")
         P.criticalkv_prepare_gram(prep, sets[0]["w_o"], gram, workspace=ws0)

@@ -15,25 +15,15 @@ import numpy as np
 REL_TOL = 2e-3
 
 
-def cfg_desc(P, cfg, *, flags=0, window_reduce=None, softmax_scale=0.0, norm=1, **over):
-    kw = dict(batch=cfg.batch, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
-              d_model=cfg.d_model, n_ctx=cfg.n_ctx, window=cfg.window, pool_kernel=cfg.pool_kernel,
-              dtype=P.CKV_BF16 if cfg.dtype == "bf16" else P.CKV_F32, flags=flags, eps=cfg.eps,
-              window_reduce=P.CKV_MEAN if window_reduce is None else window_reduce, softmax_scale=softmax_scale,
-              norm=norm)
-    kw.update(over)
-    return P.make_desc(**kw)
+def cfg_desc(P, cfg, **kw):
+    """Layer descriptor of a workload configuration (the package's own marshalling helper)."""
+    from paper_2502_03805_amd.marshal import cfg_desc as impl
+    return impl(cfg, **kw)
 
 
 def to_device(cfg, tensors: Dict[str, np.ndarray], wo_out_in: bool, device="cuda"):
-    import torch
-    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
-    out = {}
-    for name, a in tensors.items():
-        if name == "w_o" and wo_out_in:
-            a = np.ascontiguousarray(a.T)
-        out[name] = torch.from_numpy(a).to(device=device, dtype=dt).contiguous()
-    return out
+    from paper_2502_03805_amd.marshal import to_device as impl
+    return impl(cfg, tensors, wo_out_in, device)
 
 
 @dataclass
