@@ -757,3 +757,48 @@ def test_single_hip_runtime_and_side_stream(P):
         res = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, wo_out_in=True)
     assert_scores_close(res.crit, ref.crit, "crit(side stream)")
     compare_selection(res.idx, res.count, ref, cfg.budget, cfg.alpha)
+
+
+def test_two_streams_with_their_own_workspaces_run_concurrently(P):
+    """No state is shared between calls: two layers issued on two streams at once (each with its own workspace and
+    outputs, several passes deep) give bit for bit what they give one after the other."""
+    import torch
+    cfg = reduced(CONFIGS["llama32k"], 6100, d_model=1024)
+    desc = cfg_desc(P, cfg, flags=P.CKV_WO_OUT_IN)
+    b, H, Hkv, n, dh, B = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_ctx, cfg.head_dim, cfg.budget
+    layers = [to_device(cfg, make_layer(cfg, layer=0, seed_offset=s), True) for s in range(2)]
+    budget = torch.full((b, Hkv), B, dtype=torch.int32, device="cuda")
+
+    def outputs():
+        return dict(attn=torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda"),
+                    crit=torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda"),
+                    idx=torch.empty((b, Hkv, B), dtype=torch.int32, device="cuda"),
+                    count=torch.empty((b, Hkv), dtype=torch.int32, device="cuda"),
+                    k_out=torch.zeros((b, Hkv, B, dh), dtype=torch.bfloat16, device="cuda"),
+                    v_out=torch.zeros((b, Hkv, B, dh), dtype=torch.bfloat16, device="cuda"),
+                    diag=torch.empty((b, H, 8), dtype=torch.float32, device="cuda"),
+                    ws=torch.empty(P.workspace_bytes(desc, B), dtype=torch.uint8, device="cuda"))
+
+    def one_pass(dev, o, stream):
+        P.criticalkv_score(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], o["attn"], o["crit"], None, workspace=o["ws"],
+                           stream=stream)
+        P.criticalkv_select(desc, o["attn"], o["crit"], budget, cfg.alpha, B, o["idx"], o["count"], workspace=o["ws"],
+                            stream=stream)
+        P.criticalkv_compact(desc, dev["k"], dev["v"], o["idx"], o["count"], B, o["k_out"], o["v_out"], stream=stream)
+        P.criticalkv_diagnostics(desc, dev["v"], dev["w_o"], None, o["idx"], o["count"], B, o["diag"], workspace=o["ws"],
+                                 stream=stream)
+
+    serial = [outputs(), outputs()]
+    for dev, o in zip(layers, serial):
+        one_pass(dev, o, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    both = [outputs(), outputs()]
+    for _ in range(4):                      # several passes in flight on each stream
+        for dev, o, st in zip(layers, both, streams):
+            one_pass(dev, o, st)
+    torch.cuda.synchronize()
+    for o_ser, o_con in zip(serial, both):
+        for name in ("attn", "crit", "idx", "count", "k_out", "v_out", "diag"):
+            assert torch.equal(o_ser[name], o_con[name]), name
+    assert not torch.equal(serial[0]["idx"], serial[1]["idx"])
