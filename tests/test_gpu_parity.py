@@ -802,3 +802,42 @@ def test_two_streams_with_their_own_workspaces_run_concurrently(P):
         for name in ("attn", "crit", "idx", "count", "k_out", "v_out", "diag"):
             assert torch.equal(o_ser[name], o_con[name]), name
     assert not torch.equal(serial[0]["idx"], serial[1]["idx"])
+
+
+def test_profiled_score_records_every_stage_and_changes_nothing(P):
+    """criticalkv_score_profiled: same outputs as criticalkv_score; every stage's pair of events is recorded in
+    order on the launch stream (elapsed times non-negative, the projection the longest at this shape)."""
+    import ctypes
+    import torch
+    cfg = reduced(CONFIGS["llama32k"], 8200, d_model=1024)
+    t = make_layer(cfg)
+    desc = cfg_desc(P, cfg)                       # canonical W_O: the layout stage does real work
+    dev = to_device(cfg, t, False)
+    b, H, Hkv, n = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_ctx
+    ws = torch.empty(P.workspace_bytes(desc, cfg.budget), dtype=torch.uint8, device="cuda")
+    out = [dict(attn=torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda"),
+                crit=torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda")) for _ in range(2)]
+    P.criticalkv_score(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], out[0]["attn"], out[0]["crit"], None, workspace=ws)
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * len(P.STAGES))]
+    for e in events:
+        e.record()                                # creates the underlying hipEvent_t
+    torch.cuda.synchronize()
+    arr = (ctypes.c_void_p * len(events))(*[e.cuda_event for e in events])
+    P.criticalkv_score_profiled(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], out[1]["attn"], out[1]["crit"], None,
+                                workspace=ws, stage_events=arr)
+    torch.cuda.synchronize()
+    assert torch.equal(out[0]["attn"], out[1]["attn"]) and torch.equal(out[0]["crit"], out[1]["crit"])
+    ms = {name: events[2 * i].elapsed_time(events[2 * i + 1]) for i, name in enumerate(P.STAGES)}
+    assert all(v >= 0.0 for v in ms.values()), ms
+    assert ms["vproj"] == max(ms.values()) and ms["wo_layout"] > 0.0, ms
+    for i in range(len(P.STAGES) - 1):            # stages follow each other on the stream
+        assert events[2 * i + 1].elapsed_time(events[2 * i + 2]) >= 0.0
+    # a NULL entry is skipped: only the projection marked
+    arr2 = (ctypes.c_void_p * len(events))()
+    v = P.STAGES.index("vproj")
+    arr2[2 * v], arr2[2 * v + 1] = events[2 * v].cuda_event, events[2 * v + 1].cuda_event
+    P.criticalkv_score_profiled(desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], out[1]["attn"], out[1]["crit"], None,
+                                workspace=ws, stage_events=arr2)
+    torch.cuda.synchronize()
+    assert events[2 * v].elapsed_time(events[2 * v + 1]) > 0.0
+    print(f"[profiled score, n {n}] " + " ".join(f"{k}={v:.4f}ms" for k, v in ms.items()))
