@@ -276,6 +276,11 @@ def main():
     except RuntimeError as exc:  # capture not available: report it, the headline does not depend on it
         graph_ms = f"unavailable: {exc}"
     extras_ms = {k: round(float(np.median(v)), 4) for k, v in extras_ms.items()}
+    # workload statistic only (torch ops, outside every timed region): share of the pooled attention score held by
+    # the top 1 % of a kv head's entries
+    pooled = lane0["attn"].double()
+    top = torch.topk(pooled, max(1, n // 100), dim=-1).values.sum(-1) / pooled.sum(-1)
+    extras_ms["workload_top_1pct_attention_mass_mean_over_kv_heads"] = round(float(top.mean()), 4)
     if with_diag:
         dg = diag_out.double().cpu().numpy()
         f = {name: j for j, name in enumerate(P.DIAG_FIELDS)}
