@@ -23,11 +23,12 @@ __global__ __launch_bounds__(CP_THREADS) void compact_kernel(const char *__restr
     if (j >= cnt) return;
     const int i = idx[(size_t)head * max_budget + j];
     if (i < 0 || i >= n) return;
-    const bool is_v = blockIdx.z != 0;
-    const char *src = is_v ? v + (bi * vs0 + g * vs1 + (int64_t)i * vs2) * esize
-                           : k + (bi * ks0 + g * ks1 + (int64_t)i * ks2) * esize;
-    char *dst = (is_v ? v_out : k_out) + ((size_t)head * max_budget + j) * (size_t)row_bytes;
-    reinterpret_cast<uint4 *>(dst)[piece] = reinterpret_cast<const uint4 *>(src)[piece];
+    // the K piece and the V piece of the same row: one index read, two loads in flight per lane
+    const uint4 kk = reinterpret_cast<const uint4 *>(k + (bi * ks0 + g * ks1 + (int64_t)i * ks2) * esize)[piece];
+    const uint4 vv = reinterpret_cast<const uint4 *>(v + (bi * vs0 + g * vs1 + (int64_t)i * vs2) * esize)[piece];
+    const size_t o = ((size_t)head * max_budget + j) * (size_t)row_bytes;
+    reinterpret_cast<uint4 *>(k_out + o)[piece] = kk;
+    reinterpret_cast<uint4 *>(v_out + o)[piece] = vv;
 }
 
 hipError_t launch_compact(const Dims &d, int dtype, const void *k, const void *v, const int32_t *idx,
@@ -36,7 +37,7 @@ hipError_t launch_compact(const Dims &d, int dtype, const void *k, const void *v
     const int esize = dtype == CKV_F32 ? 4 : 2;
     const int row_bytes = d.dh * esize;
     const long long threads = (long long)max_budget * (row_bytes / 16);
-    dim3 grid((unsigned)((threads + CP_THREADS - 1) / CP_THREADS), d.batch * d.Hkv, 2);
+    dim3 grid((unsigned)((threads + CP_THREADS - 1) / CP_THREADS), d.batch * d.Hkv);
     hipLaunchKernelGGL(compact_kernel, grid, dim3(CP_THREADS), 0, s, (const char *)k, (const char *)v, idx, count,
                        (char *)k_out, (char *)v_out, d.Hkv, d.n, max_budget, row_bytes, d.ks[0], d.ks[1], d.ks[2],
                        d.vs[0], d.vs[1], d.vs[2], esize);
