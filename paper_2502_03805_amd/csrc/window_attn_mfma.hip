@@ -7,9 +7,11 @@
 //   reduce           per row: E = log2(sum_i 2^t_i) (+ log2 W for the window mean)
 //   pass 2 (colsum)  a^h_i = sum_w 2^(t_wi - E_w)
 //
-// Work split: one workgroup per (key chunk, kv head); one WAVE per query head of the group, holding
-// that head's window queries as MFMA fragments in registers (QB blocks of 32 rows, rows past W are
-// zero and masked).  Key tiles of 64 rows stream once per workgroup through LDS (direct global->LDS
+// Work split: one workgroup per (key chunk, kv head).  Pass 1: one WAVE per (query head of the group, block
+// of 32 window rows), holding those queries as MFMA fragments in registers (rows past W are zero and masked):
+// a window of more than 32 rows is spread over several waves (more waves in flight, fewer registers each; the
+// row statistics need no exchange).  Pass 2: one wave per query head with all its row blocks, because a key's
+// window sum runs over all of them (splitting it and adding the shares through LDS was measured slower).  Key tiles of 64 rows stream once per workgroup through LDS (direct global->LDS
 // loads, double buffered, 16-byte chunks XOR-swizzled against bank conflicts) and are read by every wave.
 //
 // v_mfma_f32_32x32x16_bf16 operand layout: a lane holds 8 consecutive k of row (A) / column (B)
@@ -29,7 +31,8 @@ constexpr int AM_DH = 128;
 constexpr int AM_TILE_KEYS = 64;
 constexpr int AM_TILE_BYTES = AM_TILE_KEYS * AM_DH * 2; // 16 KiB
 constexpr int AM_CHUNK_MIN = 256;                       // fewest keys per workgroup (the host picks 256, 512 or 1024)
-constexpr int AM_MAX_WAVES = 8;
+constexpr int AM_MAX_WAVES = 16;                       // pass 1: waves per workgroup, one per (head, 32-row block)
+constexpr int AM_COLSUM_WAVES = 8;                     // pass 2: waves per workgroup, one per head
 constexpr float AM_LOG2E = 1.4426950408889634f;
 constexpr float AM_NEG = -1.0e30f;
 
@@ -41,18 +44,21 @@ struct AttnArgs {
     const bf16_t *k;
     int H, G, n, W, chunks;
     int chunk_keys; // keys per workgroup, a multiple of the tile
+    int qbs;        // 32-row blocks of the window: a wave owns one (query head, row block)
+    int wpw;        // (head, row block) pairs per workgroup: a multiple of qbs, so a head's blocks share a workgroup
     int causal; // window row w sees keys <= n - W + w only
     float c; // scale * log2(e)
     int64_t ks0, ks1, ks2;
 };
 
-// Q fragments of one head: block qb covers window rows qb*32 .. qb*32+31 (zero past W).
+// Q fragments of one head: block qb covers window rows (qb0+qb)*32 .. +31 (zero past W).
 template <int QB>
-__device__ __forceinline__ void load_q_frags(const AttnArgs &A, int bi, int head, int l32, int half, bf16x8 (&qf)[QB][8])
+__device__ __forceinline__ void load_q_frags(const AttnArgs &A, int bi, int head, int qb0, int l32, int half,
+                                             bf16x8 (&qf)[QB][8])
 {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const int w = qb * 32 + l32;
+        const int w = (qb0 + qb) * 32 + l32;
         const bf16_t *p = A.q + (((size_t)bi * A.H + head) * A.W + min(w, A.W - 1)) * AM_DH + half * 8;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
@@ -105,8 +111,10 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_stats_mfma_kernel(Attn
     const int nw = blockDim.x >> 6;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-    const int head = g * A.G + blockIdx.z * AM_MAX_WAVES + wave;       // query head of this wave
-    const bool head_ok = blockIdx.z * AM_MAX_WAVES + wave < A.G;
+    const int vw = blockIdx.z * A.wpw + wave;               // (query head, 32-row block of the window) of this wave
+    const bool head_ok = wave < A.wpw && vw < A.G * A.qbs;
+    const int head = g * A.G + (head_ok ? vw / A.qbs : 0);
+    const int qb0 = head_ok ? vw % A.qbs : 0;
     const bf16_t *kbase = A.k + bi * A.ks0 + g * A.ks1;
     const __amdgpu_buffer_rsrc_t krsrc = make_k_rsrc(kbase, A.ks2, A.n);
     const int key_begin = chunk * A.chunk_keys;
@@ -114,7 +122,7 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_stats_mfma_kernel(Attn
     const int tiles = (key_end - key_begin + AM_TILE_KEYS - 1) / AM_TILE_KEYS;
 
     bf16x8 qf[QB][8];
-    load_q_frags<QB>(A, bi, head_ok ? head : g * A.G, l32, half, qf);
+    load_q_frags<QB>(A, bi, head, qb0, l32, half, qf);
     float m[QB], l[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) { m[qb] = AM_NEG; l[qb] = 0.f; }
@@ -142,7 +150,7 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_stats_mfma_kernel(Attn
                 // acc[j]: key key0 + 8*(j/4) + 4*half + j%4, query row l32
                 // t = acc * c with c > 0, so the block maximum of t is c * max(acc); 2^(t - m) = 2^fma(acc, c, -m)
                 if (ragged) {
-                    const int last_seen = A.causal ? A.n - A.W + qb * 32 + l32 : A.n - 1; // last key this row sees
+                    const int last_seen = A.causal ? A.n - A.W + (qb0 + qb) * 32 + l32 : A.n - 1; // last key this row sees
 #pragma unroll
                     for (int j = 0; j < 16; ++j) {
                         const int key = key0 + 8 * (j / 4) + 4 * half + (j % 4);
@@ -169,7 +177,7 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_stats_mfma_kernel(Attn
         const float mo = __shfl_xor(m[qb], 32), lo = __shfl_xor(l[qb], 32);
         const float mt = fmaxf(m[qb], mo);
         const float lt = l[qb] * __builtin_amdgcn_exp2f(m[qb] - mt) + lo * __builtin_amdgcn_exp2f(mo - mt);
-        const int w = qb * 32 + l32;
+        const int w = (qb0 + qb) * 32 + l32;
         if (head_ok && half == 0 && w < A.W) {
             float *dst = part + ((((size_t)bi * A.H + head) * A.W + w) * (size_t)A.chunks + chunk) * 2;
             dst[0] = mt;
@@ -200,7 +208,7 @@ __global__ __launch_bounds__(64) void attn_stats_reduce_log2_kernel(const float 
 
 // ---- pass 2 ---------------------------------------------------------------------------------------
 template <int QB>
-__global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_colsum_mfma_kernel(AttnArgs A, const float *__restrict__ stats,
+__global__ __launch_bounds__(64 * AM_COLSUM_WAVES) void attn_colsum_mfma_kernel(AttnArgs A, const float *__restrict__ stats,
                                                                              float *__restrict__ a_raw)
 {
     __shared__ __attribute__((aligned(1024))) char lds[2 * AM_TILE_BYTES];
@@ -208,8 +216,8 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_colsum_mfma_kernel(Att
     const int nw = blockDim.x >> 6;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-    const int head = g * A.G + blockIdx.z * AM_MAX_WAVES + wave;
-    const bool head_ok = blockIdx.z * AM_MAX_WAVES + wave < A.G;
+    const int head = g * A.G + blockIdx.z * AM_COLSUM_WAVES + wave;
+    const bool head_ok = blockIdx.z * AM_COLSUM_WAVES + wave < A.G;
     const bf16_t *kbase = A.k + bi * A.ks0 + g * A.ks1;
     const __amdgpu_buffer_rsrc_t krsrc = make_k_rsrc(kbase, A.ks2, A.n);
     const int key_begin = chunk * A.chunk_keys;
@@ -217,7 +225,7 @@ __global__ __launch_bounds__(64 * AM_MAX_WAVES) void attn_colsum_mfma_kernel(Att
     const int tiles = (key_end - key_begin + AM_TILE_KEYS - 1) / AM_TILE_KEYS;
 
     bf16x8 qf[QB][8];
-    load_q_frags<QB>(A, bi, head_ok ? head : g * A.G, l32, half, qf);
+    load_q_frags<QB>(A, bi, head_ok ? head : g * A.G, 0, l32, half, qf);
     // E of the 16 window rows a lane's accumulators belong to (+inf past W: weight 0)
     float e[QB][16];
 #pragma unroll
@@ -275,7 +283,8 @@ bool attn_mfma_supported(const Dims &d)
 // (Qwen 128K: both sweeps 20 % faster than with 256), 512 at Llama 32K, 256 below.
 static int attn_chunk_keys(const Dims &d)
 {
-    const long long per_chunk_row = (long long)d.batch * d.Hkv * ((d.G + AM_MAX_WAVES - 1) / AM_MAX_WAVES);
+    const int qbs = (d.W + 31) / 32, wpw = (AM_MAX_WAVES / qbs) * qbs;
+    const long long per_chunk_row = (long long)d.batch * d.Hkv * ((d.G * qbs + wpw - 1) / wpw);
     for (int keys = 1024; keys > AM_CHUNK_MIN; keys >>= 1)
         if (per_chunk_row * ((d.n + keys - 1) / keys) >= 512) return keys;
     return AM_CHUNK_MIN;
@@ -288,6 +297,8 @@ static AttnArgs make_args(const Dims &d, const void *q, const void *k, int chunk
     A.q = (const bf16_t *)q; A.k = (const bf16_t *)k;
     A.H = d.H; A.G = d.G; A.n = d.n; A.W = d.W; A.chunks = chunks; A.causal = d.causal;
     A.chunk_keys = attn_chunk_keys(d);
+    A.qbs = (d.W + 31) / 32;
+    A.wpw = (AM_MAX_WAVES / A.qbs) * A.qbs;
     A.c = d.scale * AM_LOG2E;
     A.ks0 = d.ks[0]; A.ks1 = d.ks[1]; A.ks2 = d.ks[2];
     return A;
@@ -296,12 +307,9 @@ static AttnArgs make_args(const Dims &d, const void *q, const void *k, int chunk
 hipError_t launch_attn_stats_mfma(const Dims &d, const void *q, const void *k, float *part, int chunks, hipStream_t s)
 {
     const AttnArgs A = make_args(d, q, k, chunks);
-    const int nw = d.G < AM_MAX_WAVES ? d.G : AM_MAX_WAVES;
-    dim3 grid(chunks, d.batch * d.Hkv, (d.G + AM_MAX_WAVES - 1) / AM_MAX_WAVES), block(64 * nw);
-    const int qb = (d.W + 31) / 32;
-    if (qb == 1) hipLaunchKernelGGL(attn_stats_mfma_kernel<1>, grid, block, 0, s, A, part);
-    else if (qb == 2) hipLaunchKernelGGL(attn_stats_mfma_kernel<2>, grid, block, 0, s, A, part);
-    else hipLaunchKernelGGL(attn_stats_mfma_kernel<3>, grid, block, 0, s, A, part);
+    const int pairs = d.G * A.qbs, nw = pairs < A.wpw ? pairs : A.wpw;
+    dim3 grid(chunks, d.batch * d.Hkv, (pairs + A.wpw - 1) / A.wpw), block(64 * nw);
+    hipLaunchKernelGGL(attn_stats_mfma_kernel<1>, grid, block, 0, s, A, part);
     return hipGetLastError();
 }
 
@@ -317,8 +325,8 @@ hipError_t launch_attn_colsum_mfma(const Dims &d, const void *q, const void *k, 
                                    hipStream_t s)
 {
     const AttnArgs A = make_args(d, q, k, mfma_attn_chunks(d));
-    const int nw = d.G < AM_MAX_WAVES ? d.G : AM_MAX_WAVES;
-    dim3 grid(A.chunks, d.batch * d.Hkv, (d.G + AM_MAX_WAVES - 1) / AM_MAX_WAVES), block(64 * nw);
+    const int nw = d.G < AM_COLSUM_WAVES ? d.G : AM_COLSUM_WAVES;
+    dim3 grid(A.chunks, d.batch * d.Hkv, (d.G + AM_COLSUM_WAVES - 1) / AM_COLSUM_WAVES), block(64 * nw);
     const int qb = (d.W + 31) / 32;
     if (qb == 1) hipLaunchKernelGGL(attn_colsum_mfma_kernel<1>, grid, block, 0, s, A, stats, a_raw);
     else if (qb == 2) hipLaunchKernelGGL(attn_colsum_mfma_kernel<2>, grid, block, 0, s, A, stats, a_raw);
