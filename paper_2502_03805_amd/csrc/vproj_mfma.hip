@@ -50,7 +50,7 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
                                                                    const bf16_t *__restrict__ w_t,
                                                                    float *__restrict__ vnorm, int H, int G, int n,
                                                                    int dm, int64_t vs0, int64_t vs1, int64_t vs2,
-                                                                   int row_tiles, int heads)
+                                                                   int row_tiles, int heads, int pair)
 {
     static_assert(VM_LOADS == VM_CB, "one direct load per wave and column block");
     __shared__ __attribute__((aligned(1024))) char lds[2 * VM_TILE_BYTES];
@@ -59,11 +59,14 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
     // pairs, i.e. heads of one kv group, and walks them two at a time: the two heads take turns on every row
     // tile, so the second one finds the tile's V rows in that L2, and the workgroups resident on the XCD stream
     // the same two 1 MiB W_O slices, which stay in L2 as well.  (Four heads in turn were measured slower: their
-    // four slices evict each other.  Measured against one head at a time: same speed, half the L2 misses.)
+    // four slices evict each other.  Measured against one head at a time: same speed, half the L2 misses -- as
+    // long as two slices leave room in L2: at d_model 5120 (2 x 1.25 MiB) pairing was 13 % slower, so the host
+    // pairs heads only up to d_model 4096.)
     const int xcd = blockIdx.x & 7, k_in_xcd = blockIdx.x >> 3;
     const int hpx = (heads + 7) >> 3;                    // heads per XCD
-    const int member = k_in_xcd & 1, pt = k_in_xcd >> 1; // which head of the pair; (pair, row tile)
-    const int in_xcd = 2 * (pt / row_tiles) + member;
+    // pair = 1: two heads take turns on a row tile; pair = 0: one head at a time (its slice alone in L2)
+    const int member = pair ? (k_in_xcd & 1) : 0, pt = pair ? (k_in_xcd >> 1) : k_in_xcd;
+    const int in_xcd = (pair ? 2 : 1) * (pt / row_tiles) + member;
     const int hb = xcd * hpx + in_xcd;                   // batch * H + head
     if (in_xcd >= hpx || hb >= heads) return;
     const int tile_x = pt % row_tiles;
@@ -196,9 +199,11 @@ static void launch_rb(const Dims &d, const void *v, const void *w_t, float *vnor
     const int rows_per_wg = VM_WAVES * RB * 16;
     const int row_tiles = (d.n + rows_per_wg - 1) / rows_per_wg;
     const int heads = d.batch * d.H;
-    const long long wgs = 8ll * 2 * ((((heads + 7) / 8) + 1) / 2) * row_tiles; // 8 XCDs x pairs of heads x row tiles
+    const int pair = (size_t)2 * VM_DH * d.dm * 2 <= ((size_t)2 << 20) ? 1 : 0; // two slices within 2 MiB
+    const int hpx = (heads + 7) / 8;
+    const long long wgs = 8ll * (pair ? 2 * ((hpx + 1) / 2) : hpx) * row_tiles; // 8 XCDs x heads (in pairs) x row tiles
     hipLaunchKernelGGL((vproj_mfma_kernel<RB>), dim3((unsigned)wgs), dim3(VM_THREADS), 0, s, (const bf16_t *)v,
-                       (const bf16_t *)w_t, vnorm, d.H, d.G, d.n, d.dm, d.vs[0], d.vs[1], d.vs[2], row_tiles, heads);
+                       (const bf16_t *)w_t, vnorm, d.H, d.G, d.n, d.dm, d.vs[0], d.vs[1], d.vs[2], row_tiles, heads, pair);
 }
 
 hipError_t launch_vproj_mfma(const Dims &d, const void *v, const void *w_t, float *vnorm, hipStream_t s)
