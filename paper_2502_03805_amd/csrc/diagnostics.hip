@@ -10,11 +10,11 @@
 // u_all = sum_i A_i v_i and u_S = sum_{S} A_i v_i: V is read once per kv head (plus the selected rows once
 // more) and W_O once per query head, instead of materialising V W_O.
 //
-//   sweep     32 workgroups per kv head, each over every 32nd 256-token chunk: partial u_all, C, M for the
+//   sweep     128 workgroups per kv head, each over every 128th 256-token chunk: partial u_all, C, M for the
 //             group's query heads
 //   selected  the same over the head's index list: partial u_S and the four sums over S1 / S2; stage-1
 //             membership is read from the selection's stage-2 key array
-//   finish    one workgroup per query head: the 32 partials summed in double in a fixed order, the
+//   finish    one workgroup per query head: the 128 partials summed in double in a fixed order, the
 //             d_h x d matrix-vector product, the norm of the result and the closed forms
 #include "common.hpp"
 
@@ -22,7 +22,7 @@ namespace ckv {
 
 constexpr int DG_THREADS = 256;
 constexpr int DG_CHUNK = 256;  // == DG_THREADS: a thread stages one token of a chunk
-constexpr int DG_PARTS = 32;   // workgroups (and partial sums) per head
+constexpr int DG_PARTS = 128;  // workgroups (and partial sums) per head
 constexpr int DG_GMAX = 8; // query heads of a group handled by one workgroup (more: blockIdx.z)
 constexpr uint32_t DG_TAKEN = 0xFFFFFFFFu; // the selection's mark for stage-1 entries in its stage-2 keys
 
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(DG_THREADS) void diag_partial_kernel(DiagArgs A)
                 }
         }
         __syncthreads();
-#pragma unroll 4
+#pragma unroll 8
         for (int jj = lane; jj < len; jj += lanes) {
             const int i = tok_s[jj];
             float x[8];
