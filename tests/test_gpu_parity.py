@@ -841,3 +841,45 @@ def test_profiled_score_records_every_stage_and_changes_nothing(P):
     torch.cuda.synchronize()
     assert events[2 * v].elapsed_time(events[2 * v + 1]) > 0.0
     print(f"[profiled score, n {n}] " + " ".join(f"{k}={v:.4f}ms" for k, v in ms.items()))
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_valid_shapes_whole_pass(P, seed):
+    """Seeded draws over the descriptor's valid range (group size, window, pool width, context with ragged tails,
+    d_model, budget, alpha, W_O layout, norm, the prefill flags): whole pass against the oracle."""
+    r = np.random.Generator(np.random.PCG64(9000 + seed))
+    bf16 = bool(r.integers(0, 2))
+    dh = 128 if bf16 and r.random() < 0.7 else 64
+    Hkv = int(r.integers(1, 4))
+    G = int(r.choice([1, 2, 3, 4, 5, 8]))
+    n = int(r.choice([r.integers(1, 64), r.integers(64, 700), r.integers(700, 5000)]))
+    W = int(min(n, r.choice([1, 2, 7, 16, 32, 33, 64, 96])))
+    dm = int(r.choice([32, 96, 128, 256, 384, 512, 640]))
+    if bf16 and dh == 128 and r.random() < 0.5:
+        dm = int(r.choice([128, 256, 512, 1024]))         # shapes the matrix-core projection covers
+    pool = int(r.choice([1, 3, 5, 7, 13]))
+    batch = int(r.integers(1, 3))
+    budget = int(r.integers(0, n + 1))
+    alpha = float(r.choice([0.0, 0.25, 0.5, 0.5, 0.75, 1.0]))
+    norm = int(r.choice([1, 1, 2]))
+    wo_out_in = bool(r.integers(0, 2))
+    causal = bool(r.integers(0, 2))
+    protect = causal and bool(r.integers(0, 2))
+    base = CONFIGS["llama32k" if bf16 else "tiny"]
+    cfg = base.with_(batch=batch, n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=dh, d_model=dm, n_ctx=n, window=W,
+                     pool_kernel=pool, budget=budget, alpha=alpha, n_sinks=min(base.n_sinks, n))
+    t = make_layer(cfg, seed_offset=seed)
+    flags = (P.CKV_CAUSAL_TAIL if causal else 0) | (P.CKV_PROTECT_WINDOW if protect else 0)
+    ref = O.full_pass(t["q_win"], t["k"], t["v"], t["w_o"], budget, alpha, pool_kernel=pool, eps=cfg.eps, norm=norm,
+                      causal_tail=causal, protect_window=protect)
+    res = run_gpu_pass(P, cfg, t, budget, alpha, flags=flags, wo_out_in=wo_out_in, norm=norm)
+    label = (f"seed {seed}: {'bf16' if bf16 else 'f32'} dh{dh} H{G * Hkv}/{Hkv} n{n} W{W} dm{dm} pool{pool} b{batch} "
+             f"B{budget} a{alpha} norm{norm} {'out_in ' if wo_out_in else ''}{'causal ' if causal else ''}{'protect' if protect else ''}")
+    e_v = assert_scores_close(res.vnorm, ref.vnorm, "vnorm " + label)
+    finite = np.isfinite(ref.crit) & (ref.crit < 1e38)    # protected entries carry the largest float on both sides
+    e_a = assert_scores_close(np.where(finite, res.attn, 0), np.where(finite, ref.attn, 0), "attn " + label)
+    e_c = assert_scores_close(np.where(finite, res.crit, 0), np.where(finite, ref.crit, 0), "crit " + label)
+    assert np.array_equal(res.crit >= 1e38, ref.crit >= 1e38)
+    swaps = compare_selection(res.idx, res.count, ref, budget, alpha)
+    assert_compaction_exact(res, t, budget)
+    print(f"[{label}] err vnorm {e_v[0]:.1e} attn {e_a[0]:.1e} crit {e_c[0]:.1e} swaps {swaps}")
