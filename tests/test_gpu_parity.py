@@ -883,3 +883,13 @@ def test_random_valid_shapes_whole_pass(P, seed):
     swaps = compare_selection(res.idx, res.count, ref, budget, alpha)
     assert_compaction_exact(res, t, budget)
     print(f"[{label}] err vnorm {e_v[0]:.1e} attn {e_a[0]:.1e} crit {e_c[0]:.1e} swaps {swaps}")
+    # the calls beside the pass on the same draw: allocation on the GPU's own scores (exact), diagnostics
+    total = int(r.integers(0, Hkv * n + 1))
+    ff = np.float32(r.choice([0.0, 0.3, 1.0]))
+    finite_attn = np.where(res.attn >= 1e38, np.float32(3.0e38), res.attn)   # protected entries stay the largest
+    assert np.array_equal(run_allocate(P, finite_attn, total, ff), O.allocate(finite_attn.astype(np.float64), total, ff))
+    if not causal and swaps == 0:
+        got, idx, _ = run_diagnostics(P, cfg, t, budget, alpha, wo_out_in=wo_out_in, norm=norm)
+        ref_d, ref_idx = oracle_diagnostics(cfg, t, budget, alpha, norm=norm)
+        assert np.array_equal(idx, ref_idx)
+        assert_diagnostics_close(got, ref_d, label)
