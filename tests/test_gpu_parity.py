@@ -361,6 +361,23 @@ def test_select_signed_zero_and_negative_keys(P):
         assert_select_exact(P, -attn, crit, B, 0.25)
 
 
+def test_select_infinities_denormals_and_extreme_magnitudes(P):
+    """Keys at the ends of the float range (both infinities, the largest and smallest normals, denormals) keep
+    their IEEE order in the radix image."""
+    r = np.random.Generator(np.random.PCG64(31))
+    n = 5000
+    specials = np.array([np.inf, -np.inf, 3.4028235e38, -3.4028235e38, 1.1754944e-38, -1.1754944e-38, 1e-45, -1e-45,
+                         1e-40, 0.0, -0.0, 1.0, -1.0], dtype=np.float32)
+    attn = r.choice(specials, (1, 3, n)).astype(np.float32)
+    crit = (r.standard_normal((1, 3, n)) * 10.0 ** r.integers(-44, 38, (1, 3, n))).astype(np.float32)
+    crit[0, :, ::97] = np.inf
+    crit[0, :, 5::101] = -np.inf
+    for B in (1, 600, 2500, n):
+        for alpha in (0.5, 0.0, 1.0):
+            assert_select_exact(P, attn, crit, B, alpha)
+            assert_select_exact(P, crit, attn, B, alpha)
+
+
 def test_budget_is_clamped_to_n_and_max_budget(P):
     n = 100
     r = np.random.Generator(np.random.PCG64(9))
