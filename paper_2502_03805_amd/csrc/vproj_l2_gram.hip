@@ -7,8 +7,10 @@
 //
 //   gram_partial  G^h over a slice of the d_model columns, fp32 on the vector ALUs (W_O is a weight:
 //                 this is a per-layer constant, a few GFLOP)
-//   gram_finish   sums the slices and splits G into two bf16 matrices G_hi + G_lo (error ~2^-17 relative),
-//                 stored [head][u][t] (G is symmetric, so a row is also a column)
+//   gram_finish   sums the slices, folds the symmetric G onto its lower block triangle (32 x 32 blocks: those
+//                 below the diagonal doubled, those above dropped -- the quadratic form is unchanged and
+//                 12 of the 32 block products fall away) and splits it into two bf16 matrices G_hi + G_lo
+//                 (error ~2^-17 relative), stored [head][u][t]
 //   l2 kernel     one workgroup per (group of row tiles, kv head): a tile's V rows stay in registers as MFMA
 //                 B fragments for all G query heads of the group (V is read once); per head the two G
 //                 matrices (64 KiB) stream through a double-buffered LDS and  Y^T = G V^T  is accumulated
@@ -83,7 +85,8 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const bf16_t *__restr
         for (int j = 0; j < 8; ++j) dst[(t0 + i) * GL_DH + u0 + j] = acc[i][j];
 }
 
-// G = sum of the slices (fixed order), split into hi + lo bf16; gram[head][0 = hi, 1 = lo][u][t]
+// G = sum of the slices (fixed order), folded onto its lower block triangle, split into hi + lo bf16;
+// gram[head][0 = hi, 1 = lo][u][t]
 __global__ __launch_bounds__(256) void gram_finish_kernel(const float *__restrict__ partial, bf16_t *__restrict__ gram)
 {
     const int h = blockIdx.x;
@@ -91,6 +94,10 @@ __global__ __launch_bounds__(256) void gram_finish_kernel(const float *__restric
         float g = 0.f;
 #pragma unroll
         for (int s = 0; s < GL_SLICES; ++s) g += partial[((size_t)h * GL_SLICES + s) * GL_DH * GL_DH + e];
+        // G is symmetric, so v G v^T = sum over the 32 x 32 blocks (bu, bt) on and below the diagonal, the ones
+        // below it counted twice: the kernel reads those blocks only (20 of the 32 block products)
+        const int bu = e >> 12, bt = (e & (GL_DH - 1)) >> 5; // e = u * 128 + t
+        g = bt < bu ? 2.f * g : bt == bu ? g : 0.f;
         const bf16_t hi = f32_to_bf16_rne(g);
         const bf16_t lo = f32_to_bf16_rne(g - bf16_to_f32(hi));
         gram[((size_t)h * 2 + 0) * GL_DH * GL_DH + e] = hi;
@@ -103,7 +110,7 @@ __global__ __launch_bounds__(256) void gram_finish_kernel(const float *__restric
 // One workgroup of 8 waves per CU.  The work of a workgroup is a sequence of steps (row tile, query head);
 // a step needs that head's two Gram matrices (64 KiB) in LDS.  The matrices are double buffered (128 KiB):
 // the loads of step k + 1 are issued before the MFMAs of step k and are waited for after them, so one barrier
-// per step is the only synchronisation and the L2 latency of the matrices hides behind 256 MFMAs per wave.
+// per step is the only synchronisation and the L2 latency of the matrices hides behind 160 MFMAs per wave.
 // A row tile's V fragments stay in registers for its G steps.
 __global__ __launch_bounds__(GL_THREADS) void vproj_l2_mfma_kernel(const bf16_t *__restrict__ v,
                                                                     const bf16_t *__restrict__ gram,
@@ -175,10 +182,12 @@ __global__ __launch_bounds__(GL_THREADS) void vproj_l2_mfma_kernel(const bf16_t 
         const int a_f = 4 * (l16 >> 2) + (l16 & 3);            // f(u) of that row: bits 3-4 and 0-1 of u
         // fragments of 16 rows of G_hi (0-3) and G_lo (4-7); read one ub ahead of their use
         bf16x8 gf[2][8];
+        // (rows of block sp meet the k-chunks s <= sp only: the stored matrices are block lower triangular)
         auto read_g = [&](int ub, bf16x8 (&dst)[8]) {
             const char *rowp = gl + (32 * (ub >> 1) + 4 * (ub & 1) + a_row) * 256;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
+                if (s > (ub >> 1)) continue; // static: the loop over ub is unrolled
                 const int slot = ((4 * s + kc) ^ a_f) * 16;
                 dst[s] = *reinterpret_cast<const bf16x8 *>(rowp + slot);
                 dst[4 + s] = *reinterpret_cast<const bf16x8 *>(rowp + GL_G_BYTES + slot);
@@ -194,7 +203,7 @@ __global__ __launch_bounds__(GL_THREADS) void vproj_l2_mfma_kernel(const bf16_t 
 #pragma unroll
             for (int rb = 0; rb < GL_RB; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
+            for (int s = 0; s <= sp; ++s) {
 #pragma unroll
                 for (int rb = 0; rb < GL_RB; ++rb)
                     acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gf[cur][4 + s], vf[rb][s], acc[rb], 0, 0, 0);
