@@ -321,7 +321,7 @@ def assert_select_exact(P, attn, crit, budget, alpha, max_budget=None):
     assert np.array_equal(idx, ref_idx)
 
 
-@pytest.mark.parametrize("n", [1, 3, 4, 5, 1000, 4096, 4097, 12289, 40000])
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 1000, 2047, 2048, 2049, 4096, 4097, 12289, 40000])
 def test_select_exact_on_random_keys(P, n):
     r = np.random.Generator(np.random.PCG64(n))
     attn = r.random((2, 3, n), dtype=np.float32)
