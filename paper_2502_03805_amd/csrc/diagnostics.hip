@@ -221,8 +221,9 @@ __global__ __launch_bounds__(DG_THREADS) void diag_partial_kernel(DiagArgs A)
     }
 }
 
-// The finish kernel has one workgroup per query head and little to do, so every wait for memory shows: it runs
-// DF_THREADS lanes and keeps many independent loads in flight in each of its three phases.
+// The finish kernel has few workgroups (DF_SLICES per query head) and little to do, so every wait for memory
+// shows: it runs DF_THREADS lanes and keeps many independent loads in flight in each of its three phases.  Every
+// workgroup of a head sums all partials (they come from L2) and takes its own slice of W_O's rows.
 constexpr int DF_THREADS = 512;
 
 template <typename T>
