@@ -64,6 +64,25 @@ class HipEvents:
         self.made = []
 
 
+def gpu_power_state():
+    """Engine-clock level and power cap of the first GPU as sysfs shows them right after the run (None where the
+    files cannot be read).  The published peaks assume 2.4 GHz; under this load the chip is power limited."""
+    import glob
+    out = {}
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))[:1]:
+        try:
+            lines = open(path).read().split("\n")
+            out["sclk_levels"] = [l.strip() for l in lines if l.strip()]
+        except OSError:
+            pass
+        for cap in glob.glob(os.path.join(os.path.dirname(path), "hwmon", "hwmon*", "power1_cap")):
+            try:
+                out["power_cap_w"] = int(open(cap).read()) / 1e6
+            except (OSError, ValueError):
+                pass
+    return out or None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -244,6 +263,7 @@ def main():
             stage_ms[name].append(ev.ms(ctypes.c_void_p(arr[2 * i]), ctypes.c_void_p(arr[2 * i + 1])))
         stage_ms["select"].append(ev.ms(e_sel0, e_sel1))
         stage_ms["compact"].append(ev.ms(e_sel1, e_cp1))
+    stage_min_ms = {k: round(float(np.min(v)), 4) for k, v in stage_ms.items()}
     stage_ms = {k: round(float(np.median(v)), 4) for k, v in stage_ms.items()}
     # the same steps replayed from HIP graphs (one captured pass per input set): the launch-bound tail of small
     # kernels is issued without per-kernel host dispatch.  Untimed extra: events recorded inside a captured graph
@@ -335,10 +355,12 @@ def main():
                    "streams": n_streams, "serial_ms_per_step": round(serial_ms_per_step, 4),
                    "graph_replay_ms_per_step": graph_ms,
                    "tokens_per_s": round(b * n / (ms_per_step * 1e-3), 1),
+                   "gpu_power_state": gpu_power_state(),
                    **({"layers": cfg.n_layers, "total_ms_all_layers": round(cfg.n_layers * ms_per_step, 3)}
                       if cfg.n_layers > 1 else {})},
         "roofline": roofline,
-        "stages_ms": stage_ms, "stages_frac_of_own_bound": stage_frac, "beside_the_pass_ms": extras_ms,
+        "stages_ms": stage_ms, "stages_min_ms": stage_min_ms, "stages_frac_of_own_bound": stage_frac,
+        "beside_the_pass_ms": extras_ms,
         "pass_lower_bound_ms": round(t_bound_ms, 4), "pass_frac_of_bound": round(t_bound_ms / ms_per_step, 4),
     }
 
