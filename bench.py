@@ -25,6 +25,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00 after calibration against a 1 GiB device copy); the runs and the
 # calibration are written up in profiles/whole_pass_llama_hbm_counters.md.  None where not measured.
 VPROJ_TRAFFIC_BYTES = {"llama32k": int(190.0 * 2**20), "llama128k": int(607.3 * 2**20)}
+# the same for the Gram-matrix kernel of the L2 variant (95.2 + 4.0 and 383.3 + 16.0 MiB)
+L2_TRAFFIC_BYTES = {"llama32k": int(99.2 * 2**20), "llama128k": int(399.3 * 2**20)}
 
 
 class HipEvents:
@@ -342,7 +344,7 @@ def main():
         roofline = {"kernel": "vproj_mfma_kernel" if args.norm == "l1" else "vproj_l2_mfma_kernel", "bound": "mfma",
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": VPROJ_TRAFFIC_BYTES.get(cfg.name) if args.norm == "l1" else None,
+                    "traffic": (VPROJ_TRAFFIC_BYTES if args.norm == "l1" else L2_TRAFFIC_BYTES).get(cfg.name),
                     "avg_launch_ms": round(vproj_avg, 4), "algorithmic_flop_per_launch": flops}
     out = {
         "metric": "M KV entries scored+selected per second (whole score->select->compact pass, one layer)",
