@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--sets", type=int, default=0, help="independent input sets rotated over the steps (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
+    ap.add_argument("--budget-sweep", action="store_true",
+                    help="also time select + compact for budgets 10/20/40 %% x alpha 0.25/0.5/0.75 on one set of scores "
+                         "(the Qwen-shaped workload's protocol); reported beside the pass, not in the value")
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the steps are issued on round-robin (independent layers overlap); 1 = serial")
     ap.add_argument("--norm", choices=["l1", "l2", "none"], default="l1",
@@ -298,6 +301,37 @@ def main():
     except RuntimeError as exc:  # capture not available: report it, the headline does not depend on it
         graph_ms = f"unavailable: {exc}"
     extras_ms = {k: round(float(np.median(v)), 4) for k, v in extras_ms.items()}
+    # The paper sweeps budget and alpha on one set of scores: `score` once (timed above), then select + compact
+    # for every (budget fraction, alpha) pair on the scores the last pass left in lane 0.  Untimed extra.
+    if args.budget_sweep:
+        from workload import budget_from_fraction
+        sweep = {}
+        bmax = budget_from_fraction(0.4, n)
+        ws_sweep = torch.empty(P.workspace_bytes(desc, bmax), dtype=torch.uint8, device="cuda")
+        idx_s = torch.empty((b, Hkv, bmax), dtype=torch.int32, device="cuda")
+        cnt_s = torch.empty((b, Hkv), dtype=torch.int32, device="cuda")
+        ko_s = torch.empty((b, Hkv, bmax, dh), dtype=sets[0]["k"].dtype, device="cuda")
+        vo_s = torch.empty_like(ko_s)
+        dev = sets[0]
+        for frac in (0.1, 0.2, 0.4):
+            Bs = budget_from_fraction(frac, n)
+            bud_s = torch.full((b, Hkv), Bs, dtype=torch.int32, device="cuda")
+            for alpha in (0.25, 0.5, 0.75):
+                ts = []
+                for _ in range(5):
+                    e0, e1 = ev.new(), ev.new()
+                    ev.record(e0, sh)
+                    P.criticalkv_select(desc, lane0["attn"], lane0["crit"], bud_s, alpha, bmax, idx_s, cnt_s,
+                                        workspace=ws_sweep, stream=stream)
+                    P.criticalkv_compact(desc, dev["k"], dev["v"], idx_s, cnt_s, bmax, ko_s, vo_s, stream=stream)
+                    ev.record(e1, sh)
+                    torch.cuda.synchronize()
+                    ts.append(ev.ms(e0, e1))
+                assert int(cnt_s.min()) == Bs and int(cnt_s.max()) == Bs
+                sweep[f"B={Bs},alpha={alpha}"] = round(float(np.median(ts)), 4)
+        extras_ms["select_compact_sweep"] = sweep
+        extras_ms["select_compact_sweep_total"] = round(sum(sweep.values()), 4)
+        del ws_sweep, idx_s, cnt_s, ko_s, vo_s
     # workload statistic only (torch ops, outside every timed region): share of the pooled attention score held by
     # the top 1 % of a kv head's entries
     pooled = lane0["attn"].double()
