@@ -492,7 +492,8 @@ def run_diagnostics(P, cfg, t, budget, alpha, *, flags=0, wo_out_in=False, norm=
 
 def oracle_diagnostics(cfg, t, budget, alpha, norm=1, window_sum=False, crit_is_attn=False):
     r = O.score(t["q_win"], t["k"], t["v"], t["w_o"], pool_kernel=cfg.pool_kernel, eps=cfg.eps, norm=norm)
-    idx, count, _, st1 = O.select(r.attn, r.attn if crit_is_attn else r.crit, budget, alpha, with_stage1=True)
+    mb = max(1, int(np.max(budget)))  # the index list the GPU side allocates has at least one slot
+    idx, count, _, st1 = O.select(r.attn, r.attn if crit_is_attn else r.crit, budget, alpha, max_budget=mb, with_stage1=True)
     return O.diagnostics(r.a_head, t["v"], t["w_o"], idx, count, st1, norm), idx
 
 
@@ -860,7 +861,8 @@ def test_profiled_score_records_every_stage_and_changes_nothing(P):
     print(f"[profiled score, n {n}] " + " ".join(f"{k}={v:.4f}ms" for k, v in ms.items()))
 
 
-@pytest.mark.parametrize("seed", range(40))
+# (the seeds past 39 are draws with W = n under a protected window, or a zero budget, found on a wider one-off run)
+@pytest.mark.parametrize("seed", list(range(40)) + [54, 57, 71, 113, 146, 181])
 def test_random_valid_shapes_whole_pass(P, seed):
     """Seeded draws over the descriptor's valid range (group size, window, pool width, context with ragged tails,
     d_model, budget, alpha, W_O layout, norm, the prefill flags): whole pass against the oracle."""
@@ -894,8 +896,11 @@ def test_random_valid_shapes_whole_pass(P, seed):
              f"B{budget} a{alpha} norm{norm} {'out_in ' if wo_out_in else ''}{'causal ' if causal else ''}{'protect' if protect else ''}")
     e_v = assert_scores_close(res.vnorm, ref.vnorm, "vnorm " + label)
     finite = np.isfinite(ref.crit) & (ref.crit < 1e38)    # protected entries carry the largest float on both sides
-    e_a = assert_scores_close(np.where(finite, res.attn, 0), np.where(finite, ref.attn, 0), "attn " + label)
-    e_c = assert_scores_close(np.where(finite, res.crit, 0), np.where(finite, ref.crit, 0), "crit " + label)
+    if finite.any():
+        e_a = assert_scores_close(np.where(finite, res.attn, 0), np.where(finite, ref.attn, 0), "attn " + label)
+        e_c = assert_scores_close(np.where(finite, res.crit, 0), np.where(finite, ref.crit, 0), "crit " + label)
+    else:  # W = n with a protected window: every entry carries the largest float
+        e_a = e_c = (0.0, 0.0)
     assert np.array_equal(res.crit >= 1e38, ref.crit >= 1e38)
     swaps = compare_selection(res.idx, res.count, ref, budget, alpha)
     assert_compaction_exact(res, t, budget)
