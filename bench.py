@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--budget-sweep", action="store_true",
                     help="also time select + compact for budgets 10/20/40 %% x alpha 0.25/0.5/0.75 on one set of scores "
                          "(the Qwen-shaped workload's protocol); reported beside the pass, not in the value")
+    ap.add_argument("--chunked-prefill", type=int, default=0, metavar="CHUNKS",
+                    help="also time a chunked prefill of the workload's context in CHUNKS chunks with eviction to the "
+                         "budget after each (causal tail, protected window); reported beside the pass")
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the steps are issued on round-robin (independent layers overlap); 1 = serial")
     ap.add_argument("--norm", choices=["l1", "l2", "none"], default="l1",
@@ -301,6 +304,34 @@ def main():
     except RuntimeError as exc:  # capture not available: report it, the headline does not depend on it
         graph_ms = f"unavailable: {exc}"
     extras_ms = {k: round(float(np.median(v)), 4) for k, v in extras_ms.items()}
+    # Chunked prefill with eviction between chunks: the prompt arrives in chunks; after each one the cache kept so
+    # far plus the chunk is scored with the chunk's last W queries (causal inside the window, the window's own
+    # tokens protected), cut to the budget and compacted.  The host loop is paper_2502_03805_amd/chunked.py; the
+    # chunks are slices of input set 0 and every chunk uses the set's window queries.  Untimed extra.
+    if args.chunked_prefill and args.norm == "l1":
+        from paper_2502_03805_amd.chunked import chunked_prefill_evict
+        n_chunks = args.chunked_prefill
+        clen = n // n_chunks
+        dev = sets[0]
+        k_chunks = [dev["k"][:, :, c * clen:(c + 1) * clen].contiguous() for c in range(n_chunks)]
+        v_chunks = [dev["v"][:, :, c * clen:(c + 1) * clen].contiguous() for c in range(n_chunks)]
+        q_wins = [dev["q_win"]] * n_chunks
+        cflags = P.CKV_WO_OUT_IN | P.CKV_CAUSAL_TAIL | P.CKV_PROTECT_WINDOW
+        mk = lambda nn: cfg_desc(cfg, flags=cflags, norm=P.CKV_NORM_L1, n_ctx=nn)
+        ts = []
+        for _ in range(3):
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            with torch.cuda.stream(stream):
+                k_c, v_c, kept = chunked_prefill_evict(mk, q_wins, k_chunks, v_chunks, dev["w_o"], B, cfg.alpha, stream=stream)
+            torch.cuda.synchronize()
+            ts.append((time.perf_counter() - c0) * 1e3)
+        assert k_c.shape[2] == min(B, n)
+        extras_ms["chunked_prefill"] = {"chunks": n_chunks, "chunk_tokens": clen, "budget": B,
+                                        "entries_scored_per_pass": min(B, n) + clen,
+                                        "passes": sum(1 for x in kept if x is not None),
+                                        "total_ms_median_of_3": round(float(np.median(ts)), 4)}
+        del k_chunks, v_chunks, k_c, v_c, kept
     # The paper sweeps budget and alpha on one set of scores: `score` once (timed above), then select + compact
     # for every (budget fraction, alpha) pair on the scores the last pass left in lane 0.  Untimed extra.
     if args.budget_sweep:
