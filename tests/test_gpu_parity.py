@@ -9,7 +9,7 @@ import pytest
 from helpers import (assert_compaction_exact, assert_scores_close, cfg_desc, compare_selection, run_gpu_pass,
                      to_device)  # noqa: F401
 from oracle import cpu_oracle as O
-from workload import CONFIGS, make_layer, reduced
+from workload import CONFIGS, budget_from_fraction, make_layer, reduced
 
 pytestmark = pytest.mark.gpu
 
@@ -695,6 +695,16 @@ def test_full_size_qwen128k_with_budget_and_alpha_sweep(P):
     cfg = CONFIGS["qwen128k"]
     sweeps = [(B, a) for B in (13107, 26214, 52429) for a in (0.25, 0.5, 0.75)]
     _full_size_check(P, cfg, make_layer(cfg), sweeps=sweeps)
+
+
+def test_full_size_one_million_tokens_ragged(P):
+    """A context far beyond the workloads' (1,000,003 entries per head: 64-bit offsets, 2 GiB buffer descriptors,
+    thousands of key chunks and selection slices, a ragged last tile everywhere), checked like the other full
+    sizes: attention on all tokens, magnitudes and criticality on sampled tokens, selection, allocation (one
+    row of 8 million keys) and compaction exactly."""
+    n = 1000003
+    cfg = CONFIGS["llama128k"].with_(n_ctx=n, budget=budget_from_fraction(0.2, n))
+    _full_size_check(P, cfg, make_layer(cfg))
 
 
 @pytest.mark.parametrize("layer", [0, 15, 31])
