@@ -85,6 +85,60 @@ def gpu_power_state():
     return out or None
 
 
+class PowerSampler:
+    """Samples the first GPU's board power (hwmon power1_input, microwatts) from a thread while a loop of passes
+    runs; the sensor is slow, so the loop has to last some tenths of a second for the reading to settle."""
+
+    def __init__(self):
+        import glob
+        files = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        self.path = files[0] if files else None
+        clk = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.clk_path = clk[0] if clk else None
+        self.samples = []
+        self.clocks = []  # MHz of the engine-clock level marked current
+        self._stop = False
+        self._thread = None
+
+    def _run(self):
+        while not self._stop:
+            try:
+                self.samples.append(int(open(self.path).read()) / 1e6)
+            except (OSError, ValueError):
+                return
+            try:
+                for line in open(self.clk_path).read().split("\n"):
+                    if line.strip().endswith("*"):
+                        self.clocks.append(float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip()))
+            except (OSError, ValueError, IndexError, TypeError):
+                pass
+            time.sleep(0.005)
+
+    def __enter__(self):
+        if self.path:
+            import threading
+            self._thread = threading.Thread(target=self._run, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        if self._thread:
+            self._thread.join()
+
+    def summary(self):
+        if not self.samples:
+            return None
+        tail = self.samples[len(self.samples) // 2:]  # the second half: the sensor has caught up with the load
+        out = {"samples": len(self.samples), "mean_w_second_half": round(sum(tail) / len(tail), 1),
+               "max_w": round(max(self.samples), 1)}
+        if self.clocks:
+            ctail = self.clocks[len(self.clocks) // 2:]
+            out["sclk_mhz_mean_second_half"] = round(sum(ctail) / len(ctail), 1)
+            out["sclk_mhz_min"] = round(min(self.clocks), 1)
+        return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -228,6 +282,13 @@ def main():
         one_pass(sets[s % nsets], lane0, none_events)
     torch.cuda.synchronize()
     serial_ms_per_step = (time.perf_counter() - s0) * 1e3 / args.steps
+    # board power under the same back-to-back loop, kept up for about 0.4 s (untimed extra)
+    power_steps = max(args.steps, int(400.0 / max(serial_ms_per_step, 1e-3)))
+    with PowerSampler() as power:
+        for s in range(power_steps):
+            one_pass(sets[s % nsets], lane0, none_events)
+        torch.cuda.synchronize()
+    power_under_load = power.summary()
     stage_ms = {name: [] for name in P.STAGES}
     stage_ms["select"], stage_ms["compact"] = [], []
     # rows beside the hot path, timed in the same untimed breakdown: adaptive budgets and the perturbation
@@ -422,7 +483,7 @@ def main():
                    "streams": n_streams, "serial_ms_per_step": round(serial_ms_per_step, 4),
                    "graph_replay_ms_per_step": graph_ms,
                    "tokens_per_s": round(b * n / (ms_per_step * 1e-3), 1),
-                   "gpu_power_state": gpu_power_state(),
+                   "gpu_power_state": gpu_power_state(), "board_power_under_load": power_under_load,
                    **({"layers": cfg.n_layers, "total_ms_all_layers": round(cfg.n_layers * ms_per_step, 3)}
                       if cfg.n_layers > 1 else {})},
         "roofline": roofline,
