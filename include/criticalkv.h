@@ -73,8 +73,10 @@ extern "C" {
 #define CKV_CAUSAL_TAIL 8u /* the window queries are the last W tokens of the prompt and attend causally:
                             window row w (position n-W+w) sees keys 0 .. n-W+w only (chunked prefill);
                             without it every window row sees all n keys (the algorithm as printed)    */
-#define CKV_PROTECT_WINDOW 16u /* the last W entries (the window's own tokens) are always kept while the
-                            budget allows: their attn and crit are set to FLT_MAX (ties: index order)   */
+#define CKV_PROTECT_WINDOW 16u /* criticalkv_select keeps the window's own tokens: the last min(W, B) entries
+                            are part of every selection, and Algorithm 1 runs on entries 0 .. n-W-1 alone
+                            with the rest of the budget, B - min(W, B) (so b' = floor(alpha * rest)).
+                            The scores written by criticalkv_score are not changed by this flag.       */
 #define CKV_ATTN_ONLY 32u /* baseline: skip the projected-value magnitude; crit is set equal to attn, so the
                             selection is attention-only Top-B for every alpha (Algorithm 2's regular
                             selection).  w_o and v are not read by criticalkv_score (may be NULL).      */
@@ -173,6 +175,8 @@ CKV_API int criticalkv_score_profiled(const ckv_layer_desc *desc, const void *q_
  *   S2  = the b'' entries with the largest crit among entries not in S1
  * Equal keys: the lower token index is taken first.  Keys are compared as IEEE floats
  * (-0 equals +0); NaN keys give an undefined selection.
+ * With CKV_PROTECT_WINDOW the result is  {last min(W, B) entries}  u  {the two stages run on entries
+ * 0 .. n-W-1 with budget B - min(W, B)}.
  *
  * in : attn, crit [batch, Hkv, n] float32 (normally criticalkv_score's outputs)
  *      budget     [batch, Hkv]    int32, DEVICE memory
@@ -183,6 +187,16 @@ CKV_API int criticalkv_score_profiled(const ckv_layer_desc *desc, const void *q_
 CKV_API int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float *crit,
                               const int32_t *budget, float alpha, int32_t max_budget, int32_t *idx,
                               int32_t *count, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Output-major copy of a canonical projection, prepared once per layer: w_o [H*d_h, d_model] ->
+ * w_out [d_model, H*d_h] (criticalkv_prepared_wo_bytes bytes, device, 16-byte aligned).  Pass w_out to
+ * criticalkv_score together with CKV_WO_OUT_IN; without this step criticalkv_score re-lays a canonical
+ * w_o out on every call (Section 3.1's d_h x d slice per head is the canonical form; the output-major form
+ * is what the projection kernel streams).  desc->flags must not carry CKV_WO_OUT_IN or CKV_WO_IS_GRAM.
+ */
+CKV_API size_t criticalkv_prepared_wo_bytes(const ckv_layer_desc *desc);
+CKV_API int criticalkv_prepare_wo(const ckv_layer_desc *desc, const void *w_o, void *w_out, void *hip_stream);
 
 /*
  * Per-head budgets from a per-batch-item total (the allocation step of Algorithm 2 line 1).

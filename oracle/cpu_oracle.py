@@ -104,23 +104,26 @@ def projected_value_norm(v, w_o, n_q_heads: int, norm: int = 1) -> np.ndarray:
     return N
 
 
-def group_keys(abar, N, n_kv_heads: int, eps: float = 1e-4, protect_last: int = 0):
+def group_keys(abar, N, n_kv_heads: int, eps: float = 1e-4):
     abar, ap = _f64(abar)
     N, Np = _f64(N)
     b, H, n = abar.shape
     attn = np.empty((b, n_kv_heads, n), dtype=np.float64)
     crit = np.empty((b, n_kv_heads, n), dtype=np.float64)
-    rc = lib().ckvo_group_keys(b, H, n_kv_heads, n, ctypes.c_double(eps), int(protect_last), ap, Np,
+    rc = lib().ckvo_group_keys(b, H, n_kv_heads, n, ctypes.c_double(eps), ap, Np,
                                attn.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
                                crit.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
     _check(rc, "group_keys")
     return attn, crit
 
 
-def select(attn, crit, budget, alpha: float, max_budget: Optional[int] = None, with_stage1: bool = False):
+def select(attn, crit, budget, alpha: float, max_budget: Optional[int] = None, with_stage1: bool = False,
+           protect_last: int = 0):
     """Two-stage selection per (batch, kv head).  Returns idx [b,Hkv,max_budget] (tail -1),
     count [b,Hkv], tau [b,Hkv,2] (smallest key taken in stage 1 / stage 2) and, with with_stage1,
-    the uint8 flags [b,Hkv,max_budget] of the entries taken in stage 1."""
+    the uint8 flags [b,Hkv,max_budget] of the entries fixed before stage 2 (stage 1, kept window).
+    protect_last = W: the last W entries are kept as they are and the algorithm runs on the entries
+    before them with what is left of the budget."""
     attn, ap = _f64(attn)
     crit, cp = _f64(crit)
     b, Hkv, n = attn.shape
@@ -133,7 +136,7 @@ def select(attn, crit, budget, alpha: float, max_budget: Optional[int] = None, w
     count = np.zeros((b, Hkv), dtype=np.int32)
     tau = np.empty((b, Hkv, 2), dtype=np.float64)
     stage1 = np.zeros((b, Hkv, max_budget), dtype=np.uint8)
-    rc = lib().ckvo_select(b * Hkv, n, ap, cp, bp, ctypes.c_double(float(alpha)), max_budget,
+    rc = lib().ckvo_select(b * Hkv, n, ap, cp, bp, ctypes.c_double(float(alpha)), int(protect_last), max_budget,
                            idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int)),
                            count.ctypes.data_as(ctypes.POINTER(ctypes.c_int)),
                            tau.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
@@ -164,15 +167,15 @@ def diagnostics(a_head, v, w_o, idx, count, stage1, norm: int = 1) -> np.ndarray
     return out
 
 
-def select_head(attn, crit, B: int, alpha: float):
-    """One head; returns (idx ascending [B], stage1 flag [B], tau[2])."""
+def select_head(attn, crit, B: int, alpha: float, protect_last: int = 0):
+    """One head; returns (idx ascending [B], fixed-before-stage-2 flag [B], tau[2])."""
     attn, ap = _f64(attn)
     crit, cp = _f64(crit)
     n = attn.shape[0]
     idx = np.empty(max(B, 1), dtype=np.int32)
     flag = np.zeros(max(B, 1), dtype=np.uint8)
     tau = np.empty(2, dtype=np.float64)
-    rc = lib().ckvo_select_head(n, ap, cp, int(B), ctypes.c_double(float(alpha)),
+    rc = lib().ckvo_select_head(n, ap, cp, int(B), ctypes.c_double(float(alpha)), int(protect_last),
                                 idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int)),
                                 flag.ctypes.data_as(ctypes.POINTER(ctypes.c_ubyte)),
                                 tau.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
@@ -219,14 +222,13 @@ class OracleResult:
 
 
 def score(q_win, k, v, w_o, *, pool_kernel: int, eps: float = 1e-4, scale: Optional[float] = None,
-          window_sum: bool = False, norm: int = 1, causal_tail: bool = False,
-          protect_window: bool = False) -> OracleResult:
+          window_sum: bool = False, norm: int = 1, causal_tail: bool = False) -> OracleResult:
     H = q_win.shape[1]
     Hkv = k.shape[1]
     a = window_attention(q_win, k, scale, window_sum, causal_tail)
     abar = maxpool1d(a, pool_kernel)
     N = projected_value_norm(v, w_o, H, norm)
-    attn, crit = group_keys(abar, N, Hkv, eps, q_win.shape[2] if protect_window else 0)
+    attn, crit = group_keys(abar, N, Hkv, eps)
     return OracleResult(a, abar, N, attn, crit)
 
 
@@ -235,8 +237,9 @@ def full_pass(q_win, k, v, w_o, budget, alpha: float, *, pool_kernel: int, eps: 
               max_budget: Optional[int] = None, causal_tail: bool = False,
               protect_window: bool = False) -> OracleResult:
     r = score(q_win, k, v, w_o, pool_kernel=pool_kernel, eps=eps, scale=scale, window_sum=window_sum, norm=norm,
-              causal_tail=causal_tail, protect_window=protect_window)
-    r.idx, r.count, r.tau = select(r.attn, r.crit, budget, alpha, max_budget)
+              causal_tail=causal_tail)
+    r.idx, r.count, r.tau = select(r.attn, r.crit, budget, alpha, max_budget,
+                                   protect_last=q_win.shape[2] if protect_window else 0)
     r.k_out = compact(k, r.idx, r.count)
     r.v_out = compact(v, r.idx, r.count)
     return r

@@ -193,11 +193,8 @@ int ckvo_projected_value_norm(int b, int H, int Hkv, int d_h, int d_model, int n
  *     crit[bi,g,i] = (1/G) sum_{h in g} (abar[bi,h,i] + eps) * N[bi,h,i]
  * With G == 1 this is exactly the paper's A and (A + eps) * ||V W^O||_1.
  *
- * protect_last > 0 (the observation-window methods the paper builds on keep the window's own tokens):
- * the last protect_last entries get both keys set to the largest float32 (FLT_MAX, as a double), so they
- * are taken first and, being equal, in index order.
  */
-int ckvo_group_keys(int b, int H, int Hkv, int n, double eps, int protect_last,
+int ckvo_group_keys(int b, int H, int Hkv, int n, double eps,
                     const double *abar, const double *N, double *attn, double *crit)
 {
     if (b < 1 || H < 1 || Hkv < 1 || H % Hkv || n < 1) return CKVO_BAD_ARG;
@@ -212,7 +209,6 @@ int ckvo_group_keys(int b, int H, int Hkv, int n, double eps, int protect_last,
                     sa += abar[o];
                     sc += (abar[o] + eps) * N[o];
                 }
-                if (i >= n - protect_last) sa = sc = 3.4028234663852886e38 * (double)G;
                 attn[((size_t)bi * Hkv + g) * (size_t)n + i] = sa / (double)G;
                 crit[((size_t)bi * Hkv + g) * (size_t)n + i] = sc / (double)G;
             }
@@ -239,38 +235,53 @@ static int ckvo_cmp_desc(const void *pa, const void *pb)
  *   stage 1: the b' entries with the largest attn        -> taken, removed
  *   stage 2: the b'' entries with the largest crit among the remaining ones
  * Ties (the paper does not order equal keys): the lower index wins.
- * idx[0..B) receives the union in ascending index order; stage1_flag[j] (may be
- * NULL) is 1 where idx[j] came from stage 1.  tau[0], tau[1] (may be NULL)
- * receive the smallest key taken in each stage (NaN for an empty stage).
+ *
+ * protect_last = W > 0 is the workflow of the observation-window methods the paper builds on (Algorithm 2 is
+ * their template): the window's own tokens, the last W entries, are kept as they are and the algorithm picks
+ * the rest of the budget among the n - W entries before them.  Written as sets:
+ *     P = the last min(W, B) entries                       (kept whatever their scores)
+ *     R = Algorithm 1 on entries 0 .. n-W-1 alone, with budget B - |P|   (so b' = floor(alpha * (B - |P|)))
+ *     S = R u P
+ * The window entries never compete in either stage and use up no part of the split.
+ *
+ * idx[0..B) receives S in ascending index order; fixed_flag[j] (may be NULL) is 1 where idx[j] was fixed
+ * before stage 2 ran, i.e. taken in stage 1 or a member of P.  tau[0], tau[1] (may be NULL) receive the
+ * smallest key taken in each stage (NaN for an empty stage).
  */
-int ckvo_select_head(int n, const double *attn, const double *crit, int B, double alpha,
-                     int *idx, unsigned char *stage1_flag, double *tau)
+int ckvo_select_head(int n, const double *attn, const double *crit, int B, double alpha, int protect_last,
+                     int *idx, unsigned char *fixed_flag, double *tau)
 {
     if (n < 1 || B < 0 || B > n || !(alpha >= 0.0) || !(alpha <= 1.0)) return CKVO_BAD_ARG;
-    const int b1 = (int)floor(alpha * (double)B);
-    const int b2 = B - b1;
+    if (protect_last < 0 || protect_last > n) return CKVO_BAD_ARG;
+    const int n_kept_window = protect_last < B ? protect_last : B; /* |P| */
+    const int m = n - protect_last;                                 /* entries 0 .. m-1 compete */
+    const int Br = B - n_kept_window;                               /* budget of Algorithm 1 */
+    const int b1 = (int)floor(alpha * (double)Br);
+    const int b2 = Br - b1;
     ckvo_pair *p = (ckvo_pair *)malloc(sizeof(ckvo_pair) * (size_t)n);
     unsigned char *taken = (unsigned char *)calloc((size_t)n, 1);
     if (!p || !taken) { free(p); free(taken); return CKVO_NO_MEM; }
     double t1 = NAN, t2 = NAN;
 
-    for (int i = 0; i < n; ++i) { p[i].key = attn[i]; p[i].idx = i; }
-    qsort(p, (size_t)n, sizeof(ckvo_pair), ckvo_cmp_desc);
+    for (int i = 0; i < m; ++i) { p[i].key = attn[i]; p[i].idx = i; }
+    qsort(p, (size_t)m, sizeof(ckvo_pair), ckvo_cmp_desc);
     for (int j = 0; j < b1; ++j) taken[p[j].idx] = 1;
     if (b1 > 0) t1 = p[b1 - 1].key;
 
-    int m = 0;
-    for (int i = 0; i < n; ++i)
-        if (!taken[i]) { p[m].key = crit[i]; p[m].idx = i; ++m; }
-    qsort(p, (size_t)m, sizeof(ckvo_pair), ckvo_cmp_desc);
+    int r = 0;
+    for (int i = 0; i < m; ++i)
+        if (!taken[i]) { p[r].key = crit[i]; p[r].idx = i; ++r; }
+    qsort(p, (size_t)r, sizeof(ckvo_pair), ckvo_cmp_desc);
     for (int j = 0; j < b2; ++j) taken[p[j].idx] = 2;
     if (b2 > 0) t2 = p[b2 - 1].key;
+
+    for (int i = n - n_kept_window; i < n; ++i) taken[i] = 3; /* P */
 
     int c = 0;
     for (int i = 0; i < n; ++i)
         if (taken[i]) {
             idx[c] = i;
-            if (stage1_flag) stage1_flag[c] = (taken[i] == 1);
+            if (fixed_flag) fixed_flag[c] = (taken[i] != 2);
             ++c;
         }
     if (tau) { tau[0] = t1; tau[1] = t2; }
@@ -282,10 +293,12 @@ int ckvo_select_head(int n, const double *attn, const double *crit, int B, doubl
 /*
  * Selection for all (batch, kv head) pairs.  attn, crit [b*Hkv, n]; budget [b*Hkv];
  * idx [b*Hkv, max_budget] (unused tail = -1); count [b*Hkv]; tau [b*Hkv, 2] or NULL;
- * stage1 [b*Hkv, max_budget] or NULL: 1 where idx[j] was taken in stage 1.
+ * stage1 [b*Hkv, max_budget] or NULL: 1 where idx[j] was fixed before stage 2 (stage 1 or the kept window).
+ * protect_last: see ckvo_select_head.
  */
 int ckvo_select(int heads, int n, const double *attn, const double *crit, const int *budget,
-                double alpha, int max_budget, int *idx, int *count, double *tau, unsigned char *stage1)
+                double alpha, int protect_last, int max_budget, int *idx, int *count, double *tau,
+                unsigned char *stage1)
 {
     int err = 0;
 #pragma omp parallel for schedule(dynamic)
@@ -299,7 +312,7 @@ int ckvo_select(int heads, int n, const double *attn, const double *crit, const 
             continue;
         }
         if (stage1) memset(stage1 + (size_t)hd * max_budget, 0, (size_t)max_budget);
-        int rc = ckvo_select_head(n, attn + (size_t)hd * n, crit + (size_t)hd * n, B, alpha, out,
+        int rc = ckvo_select_head(n, attn + (size_t)hd * n, crit + (size_t)hd * n, B, alpha, protect_last, out,
                                   stage1 ? stage1 + (size_t)hd * max_budget : NULL,
                                   tau ? tau + 2 * (size_t)hd : NULL);
         if (rc != CKVO_OK) {

@@ -23,7 +23,8 @@ CKV_OK, CKV_E_INVALID_ARG, CKV_E_UNSUPPORTED, CKV_E_WORKSPACE, CKV_E_HIP = 0, -1
 
 EXPORTS = ("criticalkv_workspace_bytes", "criticalkv_score", "criticalkv_score_profiled", "criticalkv_select",
            "criticalkv_compact", "criticalkv_strerror", "criticalkv_gram_bytes", "criticalkv_prepare_gram",
-           "criticalkv_allocate", "criticalkv_diagnostics")
+           "criticalkv_allocate", "criticalkv_diagnostics", "criticalkv_prepared_wo_bytes",
+           "criticalkv_prepare_wo")
 STAGES = ("wo_layout", "attn_stats", "attn_colsum", "vproj", "combine")
 
 
@@ -90,6 +91,10 @@ def load() -> ctypes.CDLL:
         lib.criticalkv_prepare_gram.argtypes = [dp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.criticalkv_select.restype = ctypes.c_int
         lib.criticalkv_select.argtypes = [dp, vp, vp, vp, f32, i32, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.criticalkv_prepared_wo_bytes.restype = ctypes.c_size_t
+        lib.criticalkv_prepared_wo_bytes.argtypes = [dp]
+        lib.criticalkv_prepare_wo.restype = ctypes.c_int
+        lib.criticalkv_prepare_wo.argtypes = [dp, vp, vp, vp]
         lib.criticalkv_allocate.restype = ctypes.c_int
         lib.criticalkv_allocate.argtypes = [dp, vp, i32, f32, vp, vp, ctypes.c_size_t, vp]
         lib.criticalkv_diagnostics.restype = ctypes.c_int
@@ -171,12 +176,22 @@ def criticalkv_select(desc: LayerDesc, attn, crit, budget, alpha: float, max_bud
         raise CriticalKVError(rc, "criticalkv_select")
 
 
+def prepared_wo_bytes(desc: LayerDesc) -> int:
+    return int(load().criticalkv_prepared_wo_bytes(ctypes.byref(desc)))
+
+
+def criticalkv_prepare_wo(desc: LayerDesc, w_o, w_out, *, stream=None) -> None:
+    rc = load().criticalkv_prepare_wo(ctypes.byref(desc), _ptr(w_o), _ptr(w_out), _stream(stream))
+    if rc != CKV_OK:
+        raise CriticalKVError(rc, "criticalkv_prepare_wo")
+
+
 def criticalkv_allocate(desc: LayerDesc, attn, total_budget: int, floor_frac: float, budget, *, workspace,
                         stream=None) -> None:
     rc = load().criticalkv_allocate(ctypes.byref(desc), _ptr(attn), int(total_budget), float(floor_frac), _ptr(budget),
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != CKV_OK:
-        raise CriticalKVError(rc, "criticalkv_allocate", "criticalkv_diagnostics")
+        raise CriticalKVError(rc, "criticalkv_allocate")
 
 
 DIAG_FIELDS = ("sigma", "s", "C", "theta", "theta_hat", "theta_relax", "L", "M")

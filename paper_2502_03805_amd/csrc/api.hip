@@ -253,6 +253,23 @@ int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float
     return e == hipSuccess ? CKV_OK : CKV_E_HIP;
 }
 
+size_t criticalkv_prepared_wo_bytes(const ckv_layer_desc *desc)
+{
+    Dims d;
+    if (resolve(desc, &d) != CKV_OK) return 0;
+    return (size_t)d.H * d.dh * d.dm * elem_size(desc->dtype);
+}
+
+int criticalkv_prepare_wo(const ckv_layer_desc *desc, const void *w_o, void *w_out, void *hip_stream)
+{
+    Dims d;
+    int rc = resolve(desc, &d);
+    if (rc != CKV_OK) return rc;
+    if (!w_o || !w_out || w_o == w_out || misaligned16(w_o) || misaligned16(w_out)) return CKV_E_INVALID_ARG;
+    if (desc->flags & (CKV_WO_OUT_IN | CKV_WO_IS_GRAM)) return CKV_E_INVALID_ARG;
+    return launch_transpose_wo(d, desc->dtype, w_o, w_out, (hipStream_t)hip_stream) == hipSuccess ? CKV_OK : CKV_E_HIP;
+}
+
 int criticalkv_allocate(const ckv_layer_desc *desc, const float *attn, int32_t total_budget, float floor_frac,
                         int32_t *budget, void *workspace, size_t workspace_bytes, void *hip_stream)
 {

@@ -17,7 +17,7 @@ constexpr int CB_HEADS = 8; // query heads of a group staged together (larger gr
 __global__ __launch_bounds__(CB_THREADS) void combine_kernel(const float *__restrict__ a_raw,
                                                              const float *__restrict__ vnorm, float *__restrict__ attn,
                                                              float *__restrict__ crit, int H, int G, int n, int radius,
-                                                             float eps, int protect)
+                                                             float eps)
 {
     __shared__ float tile[CB_HEADS][CB_THREADS + 2 * CB_MAX_HALO];
     const int g = blockIdx.y, bi = blockIdx.z;
@@ -65,9 +65,8 @@ __global__ __launch_bounds__(CB_THREADS) void combine_kernel(const float *__rest
     }
     if (i < n) {
         const size_t o = ((size_t)bi * Hkv + g) * (size_t)n + i;
-        const bool forced = i >= n - protect; // the window's own tokens, when they are to be kept
-        attn[o] = forced ? 3.402823466e+38f : sum_a / (float)G;
-        crit[o] = forced ? 3.402823466e+38f : sum_c / (float)G;
+        attn[o] = sum_a / (float)G;
+        crit[o] = sum_c / (float)G;
     }
 }
 
@@ -75,7 +74,7 @@ hipError_t launch_combine(const Dims &d, const float *a_raw, const float *vnorm,
 {
     dim3 grid((d.n + CB_THREADS - 1) / CB_THREADS, d.Hkv, d.batch);
     hipLaunchKernelGGL(combine_kernel, grid, dim3(CB_THREADS), 0, s, a_raw, vnorm, attn, crit, d.H, d.G, d.n,
-                       d.pool_k / 2, d.eps, d.protect);
+                       d.pool_k / 2, d.eps);
     return hipGetLastError();
 }
 

@@ -22,7 +22,7 @@ struct Dims {
     int window_sum;
     int norm; // CKV_NORM_L1 or CKV_NORM_L2
     int causal;  // window row w sees keys <= n - W + w only
-    int protect; // number of trailing entries whose keys are forced to FLT_MAX (0 or W)
+    int protect; // trailing entries the selection keeps as they are (0 or W)
     float scale, eps;
     int64_t ks[3], vs[3];
 };

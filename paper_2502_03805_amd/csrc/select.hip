@@ -3,6 +3,8 @@
 //   b' = floor(alpha * B), b'' = B - b'
 //   S1 = the b' largest attn;  S2 = the b'' largest crit among entries outside S1
 //   idx = S1 u S2 in ascending token order
+// With a kept observation window (protect = W > 0) the last min(W, B) entries are part of the result as they
+// are, and the two stages run on entries 0 .. n-W-1 with the budget that is left (B above is then that rest).
 // Top-k is an exact order statistic: a most-significant-digit radix select on an order-preserving
 // 32-bit image of the float keys (digits of 11, 11 and 10 bits).  Equal keys are taken in ascending
 // token order: after the last digit the threshold key tau and the number r of entries equal to tau that
@@ -51,6 +53,7 @@ struct SelArgs {
     int32_t *count;
     double alpha;
     int n, max_budget, n_slices;
+    int n_rank; // entries 0 .. n_rank-1 compete in the two stages (n minus the kept window)
 };
 
 // Monotone map float -> uint32 (larger float, larger key); -0 and +0 share a key.
@@ -60,11 +63,15 @@ __device__ __forceinline__ uint32_t order_key(uint32_t u)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__device__ __forceinline__ void head_budget(const SelArgs &A, int head, int &B, int &b1, int &b2)
+// B: entries the head keeps in all; kept: how many of them are the kept window's (the last `kept` entries);
+// b1, b2: the two stages' shares of the rest
+__device__ __forceinline__ void head_budget(const SelArgs &A, int head, int &B, int &b1, int &b2, int &kept)
 {
     B = max(0, min(A.budget[head], min(A.n, A.max_budget)));
-    b1 = (int)floor(A.alpha * (double)B);
-    b2 = B - b1;
+    kept = min(A.n - A.n_rank, B);
+    const int rest = B - kept;
+    b1 = (int)floor(A.alpha * (double)rest);
+    b2 = rest - b1;
 }
 
 struct SelShared {
@@ -160,8 +167,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelArgs A)
 {
     __shared__ SelShared sh;
     const int slice = blockIdx.x, head = blockIdx.y;
-    int B, b1, b2;
-    head_budget(A, head, B, b1, b2);
+    int B, b1, b2, kept;
+    head_budget(A, head, B, b1, b2, kept);
     const uint32_t want = STAGE == 0 ? (uint32_t)b1 : (uint32_t)b2;
     if (want == 0) return;
     uint32_t *hist = A.hist + ((size_t)head * 2 + STAGE) * 3 * SEL_BINS;
@@ -195,12 +202,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelArgs A)
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const uint32_t key = STAGE == 0 ? order_key(w[j]) : w[j];
-        const bool on = (i0 + j < A.n) && key != SEL_TAKEN && (key & pmask) == prefix;
+        const bool on = (i0 + j < A.n_rank) && key != SEL_TAKEN && (key & pmask) == prefix;
         if (STAGE == 1 && PASS >= 1) {
             // stage 2: entries that beat the threshold at the digit this kernel has just decided (and agree with it
             // on the digit before): the ordered write adds these per-slice counts up instead of counting again
             constexpr uint32_t M0 = DMASK0 << DSHIFT0;
-            const bool above = (i0 + j < A.n) && key != SEL_TAKEN && (key & pmask) > prefix &&
+            const bool above = (i0 + j < A.n_rank) && key != SEL_TAKEN && (key & pmask) > prefix &&
                                (PASS == 1 || (key & M0) == (prefix & M0));
             n_above += above ? 1u : 0u;
         }
@@ -250,8 +257,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_mark_kernel(SelArgs A)
 {
     __shared__ SelShared sh;
     const int slice = blockIdx.x, head = blockIdx.y;
-    int B, b1, b2;
-    head_budget(A, head, B, b1, b2);
+    int B, b1, b2, kept;
+    head_budget(A, head, B, b1, b2, kept);
     uint32_t *st1 = A.state + ((size_t)head * 2 + 0) * ST_WORDS;
     uint32_t tau1 = 0u, r1 = 0u, before = 0u;
     if (b1 > 0) { // uniform over the workgroup
@@ -279,7 +286,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_mark_kernel(SelArgs A)
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const uint32_t key = order_key(a[j]);
-        const bool valid = i0 + j < A.n;
+        const bool valid = i0 + j < A.n_rank;
         gt[j] = b1 > 0 && valid && key > tau1;
         tie[j] = b1 > 0 && valid && key == tau1;
         n_tie += tie[j] ? 1u : 0u;
@@ -292,11 +299,11 @@ __global__ __launch_bounds__(SEL_THREADS) void select_mark_kernel(SelArgs A)
     uint32_t run_digit = 0u, run_len = 0u, n_taken = 0u;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        bool taken = gt[j];
+        bool taken = gt[j] || (i0 + j >= A.n - kept && i0 + j < A.n); // the kept window carries the stage-1 mark
         if (tie[j]) { taken = rank < r1; ++rank; }
         n_taken += taken ? 1u : 0u;
         key2[j] = taken ? SEL_TAKEN : order_key(c[j]);
-        const bool on = b2 > 0 && (i0 + j < A.n) && !taken;
+        const bool on = b2 > 0 && (i0 + j < A.n_rank) && !taken;
         const uint32_t d = (key2[j] >> DSHIFT0) & DMASK0;
         if (on && run_len && d == run_digit) {
             ++run_len;
@@ -333,8 +340,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_write_kernel(SelArgs A)
 {
     __shared__ SelShared sh;
     const int slice = blockIdx.x, head = blockIdx.y;
-    int B, b1, b2;
-    head_budget(A, head, B, b1, b2);
+    int B, b1, b2, kept;
+    head_budget(A, head, B, b1, b2, kept);
     uint32_t *st2 = A.state + ((size_t)head * 2 + 1) * ST_WORDS;
     uint32_t tau2 = 0u, r2 = 0u, d2 = 0u;
     if (b2 > 0) { // uniform over the workgroup: last digit of the stage-2 threshold
@@ -380,8 +387,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_write_kernel(SelArgs A)
     uint32_t n_tie = 0u;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const bool valid = i0 + j < A.n;
-        const bool taken = valid && key[j] == SEL_TAKEN;
+        const bool valid = i0 + j < A.n_rank; // window entries outside the budget carry ordinary keys: not ranked
+        const bool taken = i0 + j < A.n && key[j] == SEL_TAKEN;
         sel[j] = taken || (b2 > 0 && valid && key[j] > tau2);
         tie[j] = b2 > 0 && valid && key[j] == tau2;
         n_tie += tie[j] ? 1u : 0u;
@@ -414,9 +421,9 @@ size_t select_workspace_words(int heads, int n)
 }
 
 // heads rows of n keys each (a row is one (batch item, kv head), or one whole batch item for the allocation)
-hipError_t launch_select_rows(int heads, int n, const float *attn, const float *crit, const int32_t *budget,
-                              float alpha, int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2,
-                              uint32_t *scratch, hipStream_t s)
+hipError_t launch_select_rows(int heads, int n, int protect, const float *attn, const float *crit,
+                              const int32_t *budget, float alpha, int max_budget, int32_t *idx, int32_t *count,
+                              uint32_t *keys2, uint32_t *scratch, hipStream_t s)
 {
     SelArgs A;
     A.attn = reinterpret_cast<const uint32_t *>(attn);
@@ -429,6 +436,7 @@ hipError_t launch_select_rows(int heads, int n, const float *attn, const float *
     A.idx = idx; A.count = count;
     A.alpha = (double)alpha;
     A.n = n; A.max_budget = max_budget;
+    A.n_rank = n - protect;
     A.n_slices = (n + SEL_SLICE - 1) / SEL_SLICE;
     A.slice_hist = A.slices + (size_t)heads * 3 * A.n_slices;
     A.slice_suf = A.slice_hist + (size_t)heads * A.n_slices * 1024;
@@ -449,7 +457,8 @@ hipError_t launch_select(const Dims &d, const float *attn, const float *crit, co
                          int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2, uint32_t *scratch,
                          hipStream_t s)
 {
-    return launch_select_rows(d.batch * d.Hkv, d.n, attn, crit, budget, alpha, max_budget, idx, count, keys2, scratch, s);
+    return launch_select_rows(d.batch * d.Hkv, d.n, d.protect, attn, crit, budget, alpha, max_budget, idx, count, keys2,
+                              scratch, s);
 }
 
 // ---- budget allocation across the kv heads of a batch item (Algorithm 2, line 1) -------------------------
@@ -490,7 +499,7 @@ hipError_t launch_allocate(const Dims &d, const float *attn, int total, float fl
     int32_t *pool_idx = tmp + 2 * d.batch;      // [batch][P]
     if (P > 0) {
         hipLaunchKernelGGL(allocate_fill_kernel, dim3((d.batch + 63) / 64), dim3(64), 0, s, pool_budget, d.batch, P);
-        hipError_t e = launch_select_rows(d.batch, d.Hkv * d.n, attn, attn, pool_budget, 1.0f, P, pool_idx, pool_count,
+        hipError_t e = launch_select_rows(d.batch, d.Hkv * d.n, 0, attn, attn, pool_budget, 1.0f, P, pool_idx, pool_count,
                                           keys2, scratch, s);
         if (e != hipSuccess) return e;
     }

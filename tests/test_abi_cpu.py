@@ -122,6 +122,18 @@ def test_null_pointers_workspace_and_ranges(lib):
     assert lib.criticalkv_compact(ctypes.byref(d), p, p, p, None, 10, p, p, None) == P.CKV_E_INVALID_ARG
 
 
+def test_prepared_wo_validates_before_any_device_call(lib):
+    d = good_desc()
+    buf = ctypes.create_string_buffer(1024)
+    p = (ctypes.addressof(buf) + 255) & ~255
+    # prepared projection
+    assert P.prepared_wo_bytes(d) == 8 * 128 * 256 * 2
+    g = lib.criticalkv_prepare_wo
+    assert g(ctypes.byref(d), None, p, None) == P.CKV_E_INVALID_ARG
+    assert g(ctypes.byref(d), p, p, None) == P.CKV_E_INVALID_ARG                      # in place
+    assert g(ctypes.byref(good_desc(flags=P.CKV_WO_OUT_IN)), p, p + 256, None) == P.CKV_E_INVALID_ARG
+
+
 def test_gram_entry_points_validate(lib):
     d = good_desc(d_model=512, norm=P.CKV_NORM_L2)
     assert P.gram_bytes(d) == 8 * 2 * 128 * 128 * 2
@@ -156,3 +168,23 @@ def test_binding_raises_with_code():
     with pytest.raises(P.CriticalKVError) as e:
         P.criticalkv_score(d, f, f, f, f, f, f, None, workspace=f, stream=FakeStream())
     assert e.value.code == P.CKV_E_UNSUPPORTED
+    # every wrapper reports its library's code (each fails validation before any device call)
+    ok = good_desc()
+    calls = {
+        "criticalkv_allocate": lambda: P.criticalkv_allocate(ok, f, 100, 1.5, f, workspace=f, stream=FakeStream()),
+        "criticalkv_select": lambda: P.criticalkv_select(ok, f, f, f, 2.0, 10, f, f, workspace=f, stream=FakeStream()),
+        "criticalkv_compact": lambda: P.criticalkv_compact(ok, f, f, f, f, 0, f, f, stream=FakeStream()),
+        "criticalkv_diagnostics": lambda: P.criticalkv_diagnostics(ok, f, f, None, f, f, 0, f, workspace=f, stream=FakeStream()),
+        "criticalkv_prepare_gram": lambda: P.criticalkv_prepare_gram(good_desc(d_model=512), None, f, workspace=f, stream=FakeStream()),
+        "criticalkv_prepare_wo": lambda: P.criticalkv_prepare_wo(ok, None, f, stream=FakeStream()),
+    }
+    for name, call in calls.items():
+        with pytest.raises(P.CriticalKVError) as e:
+            call()
+        assert e.value.code == P.CKV_E_INVALID_ARG and name in str(e.value), name
+    # too small a workspace for the allocation's pooled list
+    class Small(Fake):
+        def numel(self): return 4096
+    with pytest.raises(P.CriticalKVError) as e:
+        P.criticalkv_allocate(ok, f, 2000, 0.0, f, workspace=Small(), stream=FakeStream())
+    assert e.value.code == P.CKV_E_WORKSPACE

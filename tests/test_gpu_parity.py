@@ -149,13 +149,19 @@ def test_causal_tail_and_protected_window(P, path, n):
                       eps=cfg.eps, causal_tail=True, protect_window=True)
     res = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, flags=flags, wo_out_in=(path != "f32"))
     W = cfg.window
-    fmax = np.float32(np.finfo(np.float32).max)
-    assert np.all(res.attn[..., -W:] == fmax) and np.all(res.crit[..., -W:] == fmax)
-    assert_scores_close(res.attn[..., :-W], ref.attn[..., :-W], "attn (causal tail)")
-    assert_scores_close(res.crit[..., :-W], ref.crit[..., :-W], "crit (causal tail)")
+    # the flag changes the selection only: the scores are the plain ones
+    assert_scores_close(res.attn, ref.attn, "attn (causal tail)")
+    assert_scores_close(res.crit, ref.crit, "crit (causal tail)")
     compare_selection(res.idx, res.count, ref, cfg.budget, cfg.alpha)
     for g in range(cfg.n_kv_heads):
-        assert set(range(n - W, n)) <= set(res.idx[0, g].tolist()), "window tokens must be kept"
+        assert res.idx[0, g, -W:].tolist() == list(range(n - W, n)), "window tokens must be kept"
+    # exactly the oracle's sets on the GPU's own keys, for budgets around the window size and every split
+    for B in sorted({0, 1, W - 1, W, W + 1, cfg.budget, n - 1, n} & set(range(n + 1))):
+        for alpha in (0.0, 0.5, 1.0):
+            got, cnt, _ = run_select(P, res.attn, res.crit, B, alpha, flags=P.CKV_PROTECT_WINDOW, window=W)
+            want, wcnt, _ = O.select(res.attn.astype(np.float64), res.crit.astype(np.float64), B, np.float32(alpha),
+                                     protect_last=W, max_budget=got.shape[-1])
+            assert np.array_equal(cnt, wcnt) and np.array_equal(got, want), (B, alpha)
     # each flag alone
     ref_c = O.full_pass(t["q_win"], t["k"], t["v"], t["w_o"], cfg.budget, cfg.alpha, pool_kernel=cfg.pool_kernel,
                         eps=cfg.eps, causal_tail=True)
@@ -294,11 +300,11 @@ def test_strided_kv_views(P):
 
 
 # ------------------------------------------------------------------------------------------------ select alone
-def run_select(P, attn, crit, budget, alpha, max_budget=None):
+def run_select(P, attn, crit, budget, alpha, max_budget=None, flags=0, window=1):
     import torch
     b, Hkv, n = attn.shape
-    desc = P.make_desc(batch=b, n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=128, d_model=128, n_ctx=n, window=1,
-                       pool_kernel=1, dtype=P.CKV_BF16)
+    desc = P.make_desc(batch=b, n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=128, d_model=128, n_ctx=n, window=window,
+                       pool_kernel=1, dtype=P.CKV_BF16, flags=flags)
     budget = np.broadcast_to(np.asarray(budget, dtype=np.int32), (b, Hkv)).copy()
     mb = max_budget or max(1, int(budget.max()))
     ws = torch.empty(P.workspace_bytes(desc, mb), dtype=torch.uint8, device="cuda")
@@ -593,44 +599,64 @@ def test_odd_shapes_every_entry_point(P, shape):
 
 
 # ------------------------------------------------------------------------------------------------ full-size
-def _full_size_check(P, cfg, t, sweeps=None, layer_label=""):
-    """Full BASELINE shape in the launch configuration the benchmark times (output-major W_O).
-    attn is checked in full (the oracle's window attention is cheap); the projected norm and the
-    criticality on sampled tokens; the selection must equal the oracle's selection on the GPU's own
-    float32 keys exactly (for every (budget, alpha) of the sweep); compaction bit-exact."""
+def _kv_subset(cfg, t, kv_heads):
+    """The sub-layer made of the given kv heads: their query heads, keys, values and rows of W_O."""
+    G, dh = cfg.n_q_heads // cfg.n_kv_heads, cfg.head_dim
+    qh = np.concatenate([np.arange(g * G, (g + 1) * G) for g in kv_heads])
+    rows = np.concatenate([np.arange(h * dh, (h + 1) * dh) for h in qh])
+    return {"q_win": t["q_win"][:, qh], "k": t["k"][:, kv_heads], "v": t["v"][:, kv_heads], "w_o": t["w_o"][rows]}, qh
+
+
+def _full_size_check(P, cfg, t, sweeps=None, layer_label="", kv_heads=None):
+    """Full BASELINE shape in the launch configuration the benchmark times (output-major W_O), against the
+    float64 oracle run in full on every token (of every kv head, or of the listed ones where a whole layer is
+    more than the host can afford): all three scores element by element; the GPU's selection against the
+    ORACLE's own selection from the oracle's own scores, differences allowed only inside the 2e-3 band around the
+    oracle's stage thresholds and counted; then the same selection against the oracle's sort on the GPU's own
+    float32 keys, where it must be identical; compaction bit-exact.  Returns the number of swapped indices."""
     import torch
     res = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, wo_out_in=True)
-    a = O.window_attention(t["q_win"], t["k"])
-    abar = O.maxpool1d(a, cfg.pool_kernel)
-    r = np.random.Generator(np.random.PCG64(123))
-    rows = np.unique(np.concatenate([r.integers(0, cfg.n_ctx, 384), [0, 1, 2, 3, cfg.n_ctx - 1, cfg.n_ctx - 2]]))
-    N_s = O.projected_value_norm(t["v"][:, :, rows], t["w_o"], cfg.n_q_heads)
-    _, crit_s = O.group_keys(abar[:, :, rows], N_s, cfg.n_kv_heads, cfg.eps)
-    attn_full, _ = O.group_keys(abar, np.zeros_like(abar), cfg.n_kv_heads, cfg.eps)
-    e_a = assert_scores_close(res.attn, attn_full, "attn (all tokens)")
-    e_v = assert_scores_close(res.vnorm[:, :, rows], N_s, "vnorm (sampled tokens)")
-    e_c = assert_scores_close(res.crit[:, :, rows], crit_s, "crit (sampled tokens)")
-    ref_idx, ref_count, _ = O.select(res.attn.astype(np.float64), res.crit.astype(np.float64), cfg.budget,
-                                     np.float32(cfg.alpha))
-    assert np.array_equal(res.count, ref_count) and np.array_equal(res.idx, ref_idx)
+    if kv_heads is None:
+        sub, gs, qh = t, np.arange(cfg.n_kv_heads), np.arange(cfg.n_q_heads)
+    else:
+        gs = np.asarray(kv_heads)
+        sub, qh = _kv_subset(cfg, t, gs)
+    ref = O.score(sub["q_win"], sub["k"], sub["v"], sub["w_o"], pool_kernel=cfg.pool_kernel, eps=cfg.eps)
+    e_v = assert_scores_close(res.vnorm[:, qh], ref.vnorm, "vnorm (all tokens)")
+    e_a = assert_scores_close(res.attn[:, gs], ref.attn, "attn (all tokens)")
+    e_c = assert_scores_close(res.crit[:, gs], ref.crit, "crit (all tokens)")
+    gpu_attn64, gpu_crit64 = res.attn.astype(np.float64), res.crit.astype(np.float64)
+    total_swaps = 0
+    for k, (B, alpha) in enumerate([(cfg.budget, cfg.alpha)] + list(sweeps or [])):
+        if k == 0:
+            idx, count = res.idx, res.count
+        else:
+            idx, count, _ = run_select(P, res.attn, res.crit, B, alpha)
+        # (1) the pass against the oracle's pass: the oracle ranks its own float64 scores
+        ref.idx, ref.count, ref.tau = O.select(ref.attn, ref.crit, B, np.float32(alpha), max_budget=idx.shape[-1])
+        swaps = compare_selection(idx[:, gs], count[:, gs], ref, B, alpha)
+        total_swaps += swaps
+        # (2) the selection kernels alone: identical keys on both sides, identical sets
+        own_idx, own_count, _ = O.select(gpu_attn64, gpu_crit64, B, np.float32(alpha), max_budget=idx.shape[-1])
+        assert np.array_equal(count, own_count) and np.array_equal(idx, own_idx), (B, alpha)
+        print(f"[{cfg.name}{layer_label} full] B {B} alpha {alpha}: swaps {swaps} against the oracle's selection on "
+              f"{len(gs) * cfg.batch} heads x {cfg.n_ctx} tokens; identical on the GPU's own keys")
     assert_compaction_exact(res, t, cfg.budget)
     # the two-stage result must differ from attention-only Top-B on this workload (stage 2 is exercised)
-    top_idx, _, _ = O.select(res.attn.astype(np.float64), res.crit.astype(np.float64), cfg.budget, 1.0)
-    assert not np.array_equal(top_idx, ref_idx)
-    print(f"[{cfg.name}{layer_label} full] max rel err attn {e_a[0]:.2e} vnorm {e_v[0]:.2e} crit {e_c[0]:.2e} "
-          f"on {rows.size} sampled tokens; selection exact on {cfg.batch * cfg.n_kv_heads} heads")
+    top_idx, _, _ = O.select(gpu_attn64, gpu_crit64, cfg.budget, 1.0)
+    assert not np.array_equal(top_idx, res.idx)
+    print(f"[{cfg.name}{layer_label} full] all {cfg.n_ctx} tokens of {len(gs)} kv heads: max / median rel err "
+          f"vnorm {e_v[0]:.2e} / {e_v[1]:.2e} attn {e_a[0]:.2e} / {e_a[1]:.2e} crit {e_c[0]:.2e} / {e_c[1]:.2e}; "
+          f"swaps {total_swaps}")
     # adaptive budgets over the whole layer: one row of Hkv * n keys per batch item, exact on the GPU's own keys
     total = cfg.n_kv_heads * cfg.budget
     for ff in (np.float32(0.2), np.float32(0.0)):
         got_b = run_allocate(P, res.attn, total, ff)
-        assert np.array_equal(got_b, O.allocate(res.attn.astype(np.float64), total, ff)), ff
+        assert np.array_equal(got_b, O.allocate(gpu_attn64, total, ff)), ff
     print(f"[{cfg.name}{layer_label} full] allocated budgets (floor 0): {got_b.tolist()}")
-    for B, alpha in (sweeps or []):
-        idx, count, _ = run_select(P, res.attn, res.crit, B, alpha)
-        ref_idx, ref_count, _ = O.select(res.attn.astype(np.float64), res.crit.astype(np.float64), B, np.float32(alpha))
-        assert np.array_equal(count, ref_count) and np.array_equal(idx, ref_idx), (B, alpha)
     del res
     torch.cuda.empty_cache()
+    return total_swaps
 
 
 def test_full_size_llama32k(P):
@@ -660,8 +686,9 @@ def test_full_size_diagnostics_one_kv_group_llama32k(P):
 
 @pytest.mark.parametrize("name", ["llama32k", "llama128k"])
 def test_full_size_l2_with_prepared_gram(P, name):
-    """The launch configuration `bench.py --norm l2` times (several row tiles per workgroup): magnitudes on sampled
-    tokens against the oracle's definition, selection exact on the GPU's own keys."""
+    """The launch configuration `bench.py --norm l2` times (several row tiles per workgroup): every token's
+    magnitude and criticality against the oracle's definition (all d_model products in float64), the selection
+    against the oracle's own under the tie rule, and exactly on the GPU's own keys."""
     import torch
     cfg = CONFIGS[name]
     t = make_layer(cfg)
@@ -673,15 +700,16 @@ def test_full_size_l2_with_prepared_gram(P, name):
     dev["w_o"] = gram
     del ws
     res = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, flags=P.CKV_WO_IS_GRAM, norm=P.CKV_NORM_L2, dev=dev)
-    r = np.random.Generator(np.random.PCG64(321))
-    rows = np.unique(np.concatenate([r.integers(0, cfg.n_ctx, 256), [0, 1, 511, 512, 4095, 4096, cfg.n_ctx - 2, cfg.n_ctx - 1]]))
-    N_s = O.projected_value_norm(t["v"][:, :, rows], t["w_o"], cfg.n_q_heads, norm=2)
-    e_v = assert_scores_close(res.vnorm[:, :, rows], N_s, "vnorm L2 (sampled tokens)")
-    ref_idx, ref_count, _ = O.select(res.attn.astype(np.float64), res.crit.astype(np.float64), cfg.budget, np.float32(cfg.alpha))
-    assert np.array_equal(res.count, ref_count) and np.array_equal(res.idx, ref_idx)
+    ref = O.full_pass(t["q_win"], t["k"], t["v"], t["w_o"], cfg.budget, cfg.alpha, pool_kernel=cfg.pool_kernel,
+                      eps=cfg.eps, norm=2)
+    e_v = assert_scores_close(res.vnorm, ref.vnorm, "vnorm L2 (all tokens)")
+    e_c = assert_scores_close(res.crit, ref.crit, "crit L2 (all tokens)")
+    swaps = compare_selection(res.idx, res.count, ref, cfg.budget, cfg.alpha)
+    own_idx, own_count, _ = O.select(res.attn.astype(np.float64), res.crit.astype(np.float64), cfg.budget, np.float32(cfg.alpha))
+    assert np.array_equal(res.count, own_count) and np.array_equal(res.idx, own_idx)
     assert_compaction_exact(res, t, cfg.budget)
-    assert np.isfinite(res.vnorm).all() and (res.vnorm > 0).all()
-    print(f"[{name} L2 full] max rel err vnorm {e_v[0]:.2e} on {rows.size} sampled tokens")
+    print(f"[{name} L2 full] all tokens: max rel err vnorm {e_v[0]:.2e} crit {e_c[0]:.2e}; swaps {swaps} against the "
+          f"oracle's selection")
     del res, dev
     torch.cuda.empty_cache()
 
@@ -700,11 +728,12 @@ def test_full_size_qwen128k_with_budget_and_alpha_sweep(P):
 def test_full_size_one_million_tokens_ragged(P):
     """A context far beyond the workloads' (1,000,003 entries per head: 64-bit offsets, 2 GiB buffer descriptors,
     thousands of key chunks and selection slices, a ragged last tile everywhere), checked like the other full
-    sizes: attention on all tokens, magnitudes and criticality on sampled tokens, selection, allocation (one
-    row of 8 million keys) and compaction exactly."""
+    sizes; the oracle covers every token of the first and the last kv head (a quarter of the layer: the whole
+    of it is 34 TFLOP in float64 on the host).  Selection and allocation (one row of 8 million keys) on the GPU's
+    own keys and the compaction are compared on all heads."""
     n = 1000003
     cfg = CONFIGS["llama128k"].with_(n_ctx=n, budget=budget_from_fraction(0.2, n))
-    _full_size_check(P, cfg, make_layer(cfg))
+    _full_size_check(P, cfg, make_layer(cfg), kv_heads=[0, cfg.n_kv_heads - 1])
 
 
 @pytest.mark.parametrize("layer", [0, 15, 31])
@@ -871,7 +900,7 @@ def test_profiled_score_records_every_stage_and_changes_nothing(P):
     print(f"[profiled score, n {n}] " + " ".join(f"{k}={v:.4f}ms" for k, v in ms.items()))
 
 
-# (the seeds past 39 are draws with W = n under a protected window, or a zero budget, found on a wider one-off run)
+# (the seeds past 39 are draws with W = n under a kept window, or a zero budget, found on a wider one-off run)
 @pytest.mark.parametrize("seed", list(range(40)) + [54, 57, 71, 113, 146, 181])
 def test_random_valid_shapes_whole_pass(P, seed):
     """Seeded draws over the descriptor's valid range (group size, window, pool width, context with ragged tails,
@@ -905,21 +934,15 @@ def test_random_valid_shapes_whole_pass(P, seed):
     label = (f"seed {seed}: {'bf16' if bf16 else 'f32'} dh{dh} H{G * Hkv}/{Hkv} n{n} W{W} dm{dm} pool{pool} b{batch} "
              f"B{budget} a{alpha} norm{norm} {'out_in ' if wo_out_in else ''}{'causal ' if causal else ''}{'protect' if protect else ''}")
     e_v = assert_scores_close(res.vnorm, ref.vnorm, "vnorm " + label)
-    finite = np.isfinite(ref.crit) & (ref.crit < 1e38)    # protected entries carry the largest float on both sides
-    if finite.any():
-        e_a = assert_scores_close(np.where(finite, res.attn, 0), np.where(finite, ref.attn, 0), "attn " + label)
-        e_c = assert_scores_close(np.where(finite, res.crit, 0), np.where(finite, ref.crit, 0), "crit " + label)
-    else:  # W = n with a protected window: every entry carries the largest float
-        e_a = e_c = (0.0, 0.0)
-    assert np.array_equal(res.crit >= 1e38, ref.crit >= 1e38)
+    e_a = assert_scores_close(res.attn, ref.attn, "attn " + label)
+    e_c = assert_scores_close(res.crit, ref.crit, "crit " + label)
     swaps = compare_selection(res.idx, res.count, ref, budget, alpha)
     assert_compaction_exact(res, t, budget)
     print(f"[{label}] err vnorm {e_v[0]:.1e} attn {e_a[0]:.1e} crit {e_c[0]:.1e} swaps {swaps}")
     # the calls beside the pass on the same draw: allocation on the GPU's own scores (exact), diagnostics
     total = int(r.integers(0, Hkv * n + 1))
     ff = np.float32(r.choice([0.0, 0.3, 1.0]))
-    finite_attn = np.where(res.attn >= 1e38, np.float32(3.0e38), res.attn)   # protected entries stay the largest
-    assert np.array_equal(run_allocate(P, finite_attn, total, ff), O.allocate(finite_attn.astype(np.float64), total, ff))
+    assert np.array_equal(run_allocate(P, res.attn, total, ff), O.allocate(res.attn.astype(np.float64), total, ff))
     if not causal and swaps == 0:
         got, idx, _ = run_diagnostics(P, cfg, t, budget, alpha, wo_out_in=wo_out_in, norm=norm)
         ref_d, ref_idx = oracle_diagnostics(cfg, t, budget, alpha, norm=norm)

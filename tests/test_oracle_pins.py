@@ -96,23 +96,83 @@ def test_causal_tail_matches_explicitly_masked_softmax():
     np.testing.assert_allclose(one, O.window_attention(q[:, :, :1], k), rtol=1e-13)
 
 
-def test_protected_window_entries_are_always_selected():
+def _best_subset(candidates, size, key):
+    """Brute force: the subset of `candidates` of the given size with the largest key sum (keys distinct, so it is
+    unique); enumerates every subset."""
+    best, best_sum = None, -np.inf
+    for sub in itertools.combinations(candidates, size):
+        tot = float(sum(key[i] for i in sub))
+        if tot > best_sum:
+            best, best_sum = sub, tot
+    return set(best)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_protected_window_by_brute_force_enumeration(seed):
+    """Kept window: S = (last min(W, B) entries) u (Algorithm 1 on the entries before the window with what is left
+    of the budget).  Checked without any sort or sentinel: each stage's Top-k is found by enumerating every subset
+    of the competing entries and taking the one with the largest key sum."""
+    r = rng(100 + seed)
+    n = int(r.integers(6, 13))
+    attn = r.permutation(n).astype(np.float64) / 64.0 + 0.01          # distinct keys
+    crit = attn * r.permutation(n).astype(np.float64) + r.permutation(n) / 1024.0
+    assert len(set(crit.tolist())) == n
+    for W in (1, 2, 3, n // 2, n):
+        for B in range(0, n + 1):
+            for alpha in (0.0, 0.3, 0.5, 1.0):
+                idx, flag, tau = O.select_head(attn, crit, B, alpha, protect_last=W)
+                kept_window = set(range(n - min(W, B), n))
+                prefix = list(range(n - W))
+                left = B - len(kept_window)
+                b1 = int(np.floor(alpha * left))
+                s1 = _best_subset(prefix, b1, attn)
+                s2 = _best_subset([i for i in prefix if i not in s1], left - b1, crit)
+                assert set(idx.tolist()) == kept_window | s1 | s2, (n, W, B, alpha)
+                assert np.all(np.diff(idx) > 0) and len(idx) == B
+                # the flag marks what was fixed before stage 2: stage 1 and the kept window
+                assert set(idx[flag].tolist()) == kept_window | s1
+                if b1 > 0:
+                    assert tau[0] == min(attn[i] for i in s1)
+                if left - b1 > 0:
+                    assert tau[1] == min(crit[i] for i in s2)
+
+
+def test_protected_window_hand_worked_fixture_and_properties():
+    # the hand-worked head of tests/golden/two_stage_hand_example.txt with its last two entries as the window
+    A = N = None
+    cases = []
+    with open(os.path.join(GOLDEN, "two_stage_hand_example.txt")) as f:
+        for line in f:
+            t = line.split()
+            if t[:1] == ["A"]:
+                A = np.array([float(x) for x in t[1:]])
+            elif t[:1] == ["N"]:
+                N = np.array([float(x) for x in t[1:]])
+            elif t[:1] == ["window_case"]:
+                kv = dict(x.split("=") for x in t[1:4])
+                cases.append((int(kv["W"]), int(kv["b"]), float(kv["alpha"]), [int(x) for x in t[5:]]))
+    assert len(cases) >= 5
+    for W, B, alpha, expect in cases:
+        idx, _, _ = O.select_head(A, A * N, B, alpha, protect_last=W)
+        assert idx.tolist() == expect, (W, B, alpha)
+    # properties on a grouped layer: the scores themselves are not touched, W = 0 is the plain algorithm,
+    # the window is a subset of every selection whose budget covers it
     r = rng(6)
     b, H, Hkv, n, W = 1, 4, 2, 40, 5
-    abar = r.random((b, H, n))
-    N = r.random((b, H, n))
-    attn, crit = O.group_keys(abar, N, Hkv, 1e-4, protect_last=W)
-    assert np.all(attn[..., -W:] == np.float64(np.finfo(np.float32).max)) and np.all(crit[..., -W:] == attn[..., -W:])
-    base_attn, base_crit = O.group_keys(abar, N, Hkv, 1e-4)
-    np.testing.assert_array_equal(attn[..., :-W], base_attn[..., :-W])
+    abar, Nn = r.random((b, H, n)), r.random((b, H, n))
+    attn, crit = O.group_keys(abar, Nn, Hkv, 1e-4)
     for B in (W, W + 3, 20):
         for alpha in (0.0, 0.5, 1.0):
-            idx, count, _ = O.select(attn, crit, B, alpha)
+            idx, count, _ = O.select(attn, crit, B, alpha, protect_last=W)
+            plain, _, _ = O.select(attn[..., :n - W], crit[..., :n - W], B - W, alpha, max_budget=B)
             for g in range(Hkv):
-                assert set(range(n - W, n)) <= set(idx[0, g].tolist())
-    # a budget below the window keeps the first window tokens (equal keys: index order)
-    idx, _, _ = O.select(attn, crit, 3, 0.5)
-    assert idx[0, 0].tolist() == [n - W, n - W + 1, n - W + 2]
+                assert idx[0, g].tolist() == plain[0, g, :B - W].tolist() + list(range(n - W, n))
+    idx0, _, _ = O.select(attn, crit, 7, 0.5, protect_last=0)
+    idx1, _, _ = O.select(attn, crit, 7, 0.5)
+    assert np.array_equal(idx0, idx1)
+    # a budget below the window keeps the most recent tokens
+    idx, _, _ = O.select(attn, crit, 3, 0.5, protect_last=W)
+    assert idx[0, 0].tolist() == [n - 3, n - 2, n - 1]
 
 
 def test_theorem_3_2_masked_softmax_identity():
