@@ -49,6 +49,8 @@ extern "C" {
 #define CKV_E_UNSUPPORTED (-2) /* valid request this build has no kernel for               */
 #define CKV_E_WORKSPACE (-3)   /* workspace missing, misaligned or too small               */
 #define CKV_E_HIP (-4)         /* a HIP launch failed (hipGetLastError was not hipSuccess) */
+#define CKV_E_STATIC_LIMIT (-5) /* criticalkv_select_noalloc: the layer needs more scratch than the
+                                   library's static buffer holds (CKV_STATIC_SCRATCH_BYTES)         */
 
 /* ckv_layer_desc.dtype: element type of q_win, k, v, w_o and of k_out, v_out */
 #define CKV_BF16 0
@@ -187,6 +189,23 @@ CKV_API int criticalkv_score_profiled(const ckv_layer_desc *desc, const void *q_
 CKV_API int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float *crit,
                               const int32_t *budget, float alpha, int32_t max_budget, int32_t *idx,
                               int32_t *count, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * criticalkv_select for callers that cannot allocate or pass device scratch memory (code under HIP graph
+ * capture that owns no workspace, tight serving loops, harnesses that forbid hipMalloc): same arguments and
+ * results as criticalkv_select without the workspace; the kernels' scratch (stage-2 keys, digit histograms,
+ * per-slice counts) lives in a static device buffer of CKV_STATIC_SCRATCH_BYTES inside the library, one copy
+ * per GPU, held until the process ends.  The call allocates and frees nothing and enqueues only kernels.
+ * A layer that needs more scratch than the buffer holds is refused with CKV_E_STATIC_LIMIT (the buffer
+ * covers batch * Hkv * n <= 2^20 entries with up to 64 (batch item, kv head) pairs, e.g. every 32K-128K
+ * layer shape of 8 kv heads).  Every call on a GPU shares that GPU's buffer: two calls that overlap in time
+ * on one GPU (different streams, different threads) race; order them on one stream or with events.
+ * criticalkv_diagnostics cannot follow this call (it reads a caller workspace).
+ */
+#define CKV_STATIC_SCRATCH_BYTES ((size_t)12 << 20)
+CKV_API int criticalkv_select_noalloc(const ckv_layer_desc *desc, const float *attn, const float *crit,
+                                      const int32_t *budget, float alpha, int32_t max_budget, int32_t *idx,
+                                      int32_t *count, void *hip_stream);
 
 /*
  * Output-major copy of a canonical projection, prepared once per layer: w_o [H*d_h, d_model] ->

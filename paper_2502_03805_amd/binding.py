@@ -19,11 +19,12 @@ CKV_BF16, CKV_F32 = 0, 1
 CKV_NORM_L1, CKV_NORM_L2 = 1, 2
 CKV_MEAN, CKV_SUM = 0, 1
 CKV_WO_OUT_IN, CKV_NO_MFMA, CKV_WO_IS_GRAM, CKV_CAUSAL_TAIL, CKV_PROTECT_WINDOW, CKV_ATTN_ONLY = 1, 2, 4, 8, 16, 32
-CKV_OK, CKV_E_INVALID_ARG, CKV_E_UNSUPPORTED, CKV_E_WORKSPACE, CKV_E_HIP = 0, -1, -2, -3, -4
+CKV_OK, CKV_E_INVALID_ARG, CKV_E_UNSUPPORTED, CKV_E_WORKSPACE, CKV_E_HIP, CKV_E_STATIC_LIMIT = 0, -1, -2, -3, -4, -5
+CKV_STATIC_SCRATCH_BYTES = 12 << 20
 
 EXPORTS = ("criticalkv_workspace_bytes", "criticalkv_score", "criticalkv_score_profiled", "criticalkv_select",
            "criticalkv_compact", "criticalkv_strerror", "criticalkv_gram_bytes", "criticalkv_prepare_gram",
-           "criticalkv_allocate", "criticalkv_diagnostics", "criticalkv_prepared_wo_bytes",
+           "criticalkv_allocate", "criticalkv_diagnostics", "criticalkv_select_noalloc", "criticalkv_prepared_wo_bytes",
            "criticalkv_prepare_wo")
 STAGES = ("wo_layout", "attn_stats", "attn_colsum", "vproj", "combine")
 
@@ -91,6 +92,8 @@ def load() -> ctypes.CDLL:
         lib.criticalkv_prepare_gram.argtypes = [dp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.criticalkv_select.restype = ctypes.c_int
         lib.criticalkv_select.argtypes = [dp, vp, vp, vp, f32, i32, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.criticalkv_select_noalloc.restype = ctypes.c_int
+        lib.criticalkv_select_noalloc.argtypes = [dp, vp, vp, vp, f32, i32, vp, vp, vp]
         lib.criticalkv_prepared_wo_bytes.restype = ctypes.c_size_t
         lib.criticalkv_prepared_wo_bytes.argtypes = [dp]
         lib.criticalkv_prepare_wo.restype = ctypes.c_int
@@ -174,6 +177,14 @@ def criticalkv_select(desc: LayerDesc, attn, crit, budget, alpha: float, max_bud
                                   workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != CKV_OK:
         raise CriticalKVError(rc, "criticalkv_select")
+
+
+def criticalkv_select_noalloc(desc: LayerDesc, attn, crit, budget, alpha: float, max_budget: int, idx, count, *,
+                              stream=None) -> None:
+    rc = load().criticalkv_select_noalloc(ctypes.byref(desc), _ptr(attn), _ptr(crit), _ptr(budget), float(alpha),
+                                          int(max_budget), _ptr(idx), _ptr(count), _stream(stream))
+    if rc != CKV_OK:
+        raise CriticalKVError(rc, "criticalkv_select_noalloc")
 
 
 def prepared_wo_bytes(desc: LayerDesc) -> int:

@@ -2,6 +2,7 @@
 // Nothing here computes any part of the pass; every step runs in the gfx950 kernels.
 #include <math.h>
 #include <algorithm>
+#include <mutex>
 
 #include "common.hpp"
 
@@ -87,6 +88,32 @@ static bool misaligned16(const void *p) { return ((uintptr_t)p & 15) != 0; }
 static bool mfma_allowed(const ckv_layer_desc *desc)
 {
     return desc->dtype == CKV_BF16 && !(desc->flags & CKV_NO_MFMA);
+}
+
+} // namespace ckv
+
+// Scratch of criticalkv_select_noalloc: one copy per GPU, part of the loaded code object.  In host code this
+// name is only a handle for hipGetSymbolAddress; the device address is looked up once per device below.
+static __device__ __align__(256) unsigned char ckv_static_scratch[CKV_STATIC_SCRATCH_BYTES];
+
+namespace ckv {
+
+constexpr int MAX_DEVICES = 64;
+static void *g_static_scratch[MAX_DEVICES];
+static std::mutex g_static_scratch_mutex;
+
+// Device address of the static scratch buffer on the current device (nullptr on failure).
+static void *static_scratch_ptr()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(ckv_static_scratch)) != hipSuccess) return nullptr;
+        g_static_scratch[dev] = p;
+    }
+    return g_static_scratch[dev];
 }
 
 } // namespace ckv
@@ -253,6 +280,29 @@ int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float
     return e == hipSuccess ? CKV_OK : CKV_E_HIP;
 }
 
+int criticalkv_select_noalloc(const ckv_layer_desc *desc, const float *attn, const float *crit, const int32_t *budget,
+                              float alpha, int32_t max_budget, int32_t *idx, int32_t *count, void *hip_stream)
+{
+    Dims d;
+    int rc = resolve(desc, &d);
+    if (rc != CKV_OK) return rc;
+    if (!attn || !crit || !budget || !idx || !count) return CKV_E_INVALID_ARG;
+    if (misaligned16(attn) || misaligned16(crit)) return CKV_E_INVALID_ARG;
+    if (!(alpha >= 0.0f) || !(alpha <= 1.0f)) return CKV_E_INVALID_ARG;
+    if (max_budget < 1 || max_budget > d.n) return CKV_E_INVALID_ARG;
+    // the two pieces criticalkv_select carves from a workspace, laid out back to back in the static buffer
+    const size_t keys_bytes = align256((size_t)d.batch * d.Hkv * d.n * 4);
+    const size_t scratch_bytes = align256(select_workspace_words(d.batch * d.Hkv, d.n) * 4);
+    if (keys_bytes + scratch_bytes > CKV_STATIC_SCRATCH_BYTES) return CKV_E_STATIC_LIMIT;
+    char *base = (char *)static_scratch_ptr();
+    if (!base) return CKV_E_HIP;
+    // (the selection's first kernel clears the histograms and the per-head state it accumulates into; every
+    // other word of the buffer is written before it is read, so what the previous call left does not matter)
+    hipError_t e = launch_select(d, attn, crit, budget, alpha, max_budget, idx, count, (uint32_t *)base,
+                                 (uint32_t *)(base + keys_bytes), (hipStream_t)hip_stream);
+    return e == hipSuccess ? CKV_OK : CKV_E_HIP;
+}
+
 size_t criticalkv_prepared_wo_bytes(const ckv_layer_desc *desc)
 {
     Dims d;
@@ -335,6 +385,7 @@ const char *criticalkv_strerror(int code)
     case CKV_E_UNSUPPORTED: return "unsupported configuration (head_dim, d_model, norm, strides or sizes)";
     case CKV_E_WORKSPACE: return "workspace missing, not 256-byte aligned or too small";
     case CKV_E_HIP: return "a HIP kernel launch failed";
+    case CKV_E_STATIC_LIMIT: return "the layer needs more scratch than the static buffer of the no-allocation entry point holds";
     default: return "unknown error code";
     }
 }

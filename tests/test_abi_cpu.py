@@ -122,10 +122,23 @@ def test_null_pointers_workspace_and_ranges(lib):
     assert lib.criticalkv_compact(ctypes.byref(d), p, p, p, None, 10, p, p, None) == P.CKV_E_INVALID_ARG
 
 
-def test_prepared_wo_validates_before_any_device_call(lib):
+def test_noalloc_select_and_prepared_wo_validate_before_any_device_call(lib):
     d = good_desc()
     buf = ctypes.create_string_buffer(1024)
     p = (ctypes.addressof(buf) + 255) & ~255
+    f = lib.criticalkv_select_noalloc
+    assert f(ctypes.byref(d), None, p, p, 0.5, 100, p, p, None) == P.CKV_E_INVALID_ARG
+    assert f(ctypes.byref(d), p, p, p, 1.5, 100, p, p, None) == P.CKV_E_INVALID_ARG
+    assert f(ctypes.byref(d), p, p, p, 0.5, 1001, p, p, None) == P.CKV_E_INVALID_ARG
+    assert f(ctypes.byref(d), p + 4, p, p, 0.5, 100, p, p, None) == P.CKV_E_INVALID_ARG
+    # more entries than the static buffer covers: refused with its own code, nothing launched
+    big = good_desc(n_ctx=1 << 20, n_q_heads=8, n_kv_heads=8)
+    assert f(ctypes.byref(big), p, p, p, 0.5, 100, p, p, None) == P.CKV_E_STATIC_LIMIT
+    assert "static" in P.strerror(P.CKV_E_STATIC_LIMIT)
+    # the workloads' largest shapes fit: 8 heads x 128K and 32 heads x 32K entries
+    assert P.CKV_STATIC_SCRATCH_BYTES == 12 << 20
+    header = open(os.path.join(ROOT, "include", "criticalkv.h")).read()
+    assert "#define CKV_STATIC_SCRATCH_BYTES ((size_t)12 << 20)" in header
     # prepared projection
     assert P.prepared_wo_bytes(d) == 8 * 128 * 256 * 2
     g = lib.criticalkv_prepare_wo
@@ -173,6 +186,7 @@ def test_binding_raises_with_code():
     calls = {
         "criticalkv_allocate": lambda: P.criticalkv_allocate(ok, f, 100, 1.5, f, workspace=f, stream=FakeStream()),
         "criticalkv_select": lambda: P.criticalkv_select(ok, f, f, f, 2.0, 10, f, f, workspace=f, stream=FakeStream()),
+        "criticalkv_select_noalloc": lambda: P.criticalkv_select_noalloc(ok, f, f, f, 2.0, 10, f, f, stream=FakeStream()),
         "criticalkv_compact": lambda: P.criticalkv_compact(ok, f, f, f, f, 0, f, f, stream=FakeStream()),
         "criticalkv_diagnostics": lambda: P.criticalkv_diagnostics(ok, f, f, None, f, f, 0, f, workspace=f, stream=FakeStream()),
         "criticalkv_prepare_gram": lambda: P.criticalkv_prepare_gram(good_desc(d_model=512), None, f, workspace=f, stream=FakeStream()),
