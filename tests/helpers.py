@@ -12,7 +12,7 @@ from typing import Dict, Optional
 
 import numpy as np
 
-REL_TOL = 2e-3
+from oracle.parity_rules import REL_TOL, assert_scores_close, compare_selection, score_errors  # noqa: F401
 
 
 def cfg_desc(P, cfg, **kw):
@@ -64,50 +64,6 @@ def run_gpu_pass(P, cfg, tensors, budget, alpha, *, flags=0, wo_out_in=False, ma
     torch.cuda.synchronize()
     return GpuResult(attn.cpu().numpy(), crit.cpu().numpy(), None if vnorm is None else vnorm.cpu().numpy(),
                      idx.cpu().numpy(), count.cpu().numpy(), k_out.float().cpu().numpy(), v_out.float().cpu().numpy())
-
-
-def score_errors(got: np.ndarray, ref: np.ndarray):
-    """max and median relative error with the floor 1e-7 * max|ref| on the denominator."""
-    ref = np.asarray(ref, dtype=np.float64)
-    got = np.asarray(got, dtype=np.float64)
-    denom = np.maximum(np.abs(ref), 1e-7 * np.abs(ref).max())
-    rel = np.abs(got - ref) / denom
-    return float(rel.max()), float(np.median(rel))
-
-
-def assert_scores_close(got, ref, what, tol=REL_TOL):
-    mx, med = score_errors(got, ref)
-    assert mx <= tol, f"{what}: max relative error {mx:.3e} > {tol} (median {med:.3e})"
-    return mx, med
-
-
-def compare_selection(idx_gpu, count_gpu, oracle, budget, alpha, tol=REL_TOL):
-    """Set comparison per (batch, kv head) under the tie rule.  Returns the total number of swapped
-    indices (entries in exactly one of the two sets); raises on any difference outside the tolerance band."""
-    b, Hkv, _ = idx_gpu.shape
-    budget = np.broadcast_to(np.asarray(budget, dtype=np.int64), (b, Hkv))
-    swaps = 0
-    for bi in range(b):
-        for g in range(Hkv):
-            B = int(budget[bi, g])
-            assert int(count_gpu[bi, g]) == B, f"count[{bi},{g}] = {count_gpu[bi, g]} != budget {B}"
-            got = idx_gpu[bi, g, :B]
-            assert np.all(idx_gpu[bi, g, B:] == -1), "tail must be -1"
-            assert np.all(np.diff(got) > 0), "indices must be strictly ascending"
-            ref = oracle.idx[bi, g, :B]
-            if np.array_equal(got, ref):
-                continue
-            diff = np.setxor1d(got, ref)
-            tau1, tau2 = oracle.tau[bi, g]
-            a = oracle.attn[bi, g, diff]
-            c = oracle.crit[bi, g, diff]
-            near1 = np.abs(a - tau1) <= tol * abs(tau1) if np.isfinite(tau1) else np.zeros(len(diff), bool)
-            near2 = np.abs(c - tau2) <= tol * abs(tau2) if np.isfinite(tau2) else np.zeros(len(diff), bool)
-            bad = diff[~(near1 | near2)]
-            assert bad.size == 0, (f"head ({bi},{g}): {bad.size} differing indices outside the tolerance band, "
-                                   f"e.g. {bad[:5].tolist()}")
-            swaps += int(diff.size)
-    return swaps
 
 
 def assert_compaction_exact(res: GpuResult, tensors, budget):
