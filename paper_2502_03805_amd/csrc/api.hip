@@ -170,22 +170,28 @@ static int score_impl(const ckv_layer_desc *desc, const void *q_win, const void 
         w_t = base + ws.w_t;
     }
     mark(ev, 2 * CKV_STAGE_WO_LAYOUT + 1, s);
-    const bool mfma_a = mfma_allowed(desc) && attn_mfma_supported(d);
+    // matrix-core attention: one wave per query head over shared key tiles where a kv group has at most four
+    // 32-row blocks of window queries (the 4:1 group with a 32-row window), wave-private key streams otherwise
+    const int row_blocks = d.G * ((d.W + 31) / 32);
+    const bool tile_a = mfma_allowed(desc) && attn_mfma_supported(d) && (row_blocks <= 4 || !attn_wave_supported(d));
+    const bool wave_a = mfma_allowed(desc) && !tile_a && attn_wave_supported(d);
     const bool mfma_v = mfma_allowed(desc) && vproj_mfma_supported(d);
-    const int chunks = mfma_a ? mfma_attn_chunks(d) : generic_attn_chunks(d);
+    const int chunks = tile_a ? mfma_attn_chunks(d) : wave_a ? wave_attn_chunks(d) : generic_attn_chunks(d);
     if (chunks > ws.max_chunks) return CKV_E_WORKSPACE;
 
     mark(ev, 2 * CKV_STAGE_ATTN_STATS, s);
-    e = mfma_a ? launch_attn_stats_mfma(d, q_win, k, part, chunks, s)
-               : launch_attn_stats_generic(d, desc->dtype, q_win, k, part, chunks, s);
+    e = tile_a ? launch_attn_stats_mfma(d, q_win, k, part, chunks, s)
+        : wave_a ? launch_attn_stats_wave(d, q_win, k, part, chunks, s)
+                 : launch_attn_stats_generic(d, desc->dtype, q_win, k, part, chunks, s);
     if (e != hipSuccess) return CKV_E_HIP;
-    e = mfma_a ? launch_attn_stats_reduce_log2(d, part, chunks, stats, s)
-               : launch_attn_stats_reduce(d, part, chunks, stats, s);
+    e = (tile_a || wave_a) ? launch_attn_stats_reduce_log2(d, part, chunks, stats, s)
+                           : launch_attn_stats_reduce(d, part, chunks, stats, s);
     if (e != hipSuccess) return CKV_E_HIP;
     mark(ev, 2 * CKV_STAGE_ATTN_STATS + 1, s);
     mark(ev, 2 * CKV_STAGE_ATTN_COLSUM, s);
-    e = mfma_a ? launch_attn_colsum_mfma(d, q_win, k, stats, a_raw, s)
-               : launch_attn_colsum_generic(d, desc->dtype, q_win, k, stats, a_raw, s);
+    e = tile_a ? launch_attn_colsum_mfma(d, q_win, k, stats, a_raw, s)
+        : wave_a ? launch_attn_colsum_wave(d, q_win, k, stats, a_raw, s)
+                 : launch_attn_colsum_generic(d, desc->dtype, q_win, k, stats, a_raw, s);
     if (e != hipSuccess) return CKV_E_HIP;
     mark(ev, 2 * CKV_STAGE_ATTN_COLSUM + 1, s);
     mark(ev, 2 * CKV_STAGE_VPROJ, s);

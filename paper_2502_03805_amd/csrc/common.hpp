@@ -43,10 +43,12 @@ struct Workspace {
     int max_chunks;    // capacity of stats_part per window row
 };
 
-constexpr int ATTN_MIN_CHUNK = 256; // fewest keys any attention kernel gives one workgroup (sizes stats_part)
+constexpr int ATTN_MIN_CHUNK = 128; // fewest keys any attention kernel gives one workgroup (sizes stats_part)
 int generic_attn_chunks(const Dims &d);
 int mfma_attn_chunks(const Dims &d);
-bool attn_mfma_supported(const Dims &d);  // shapes the matrix-core attention kernels cover
+bool attn_mfma_supported(const Dims &d);  // shapes the matrix-core attention kernels cover (shared key tiles)
+bool attn_wave_supported(const Dims &d);  // shapes the wave-private matrix-core attention kernels cover
+int wave_attn_chunks(const Dims &d);
 bool vproj_mfma_supported(const Dims &d); // shapes the matrix-core projection kernel covers
 
 Workspace carve_workspace(const Dims &d, int dtype, bool need_wt, int max_budget);
@@ -65,6 +67,10 @@ hipError_t launch_attn_stats_mfma(const Dims &d, const void *q, const void *k, f
 // matrix-core path: partials are in the log2 domain; per row E = log2(sum 2^t) (+ log2 W for the mean)
 hipError_t launch_attn_stats_reduce_log2(const Dims &d, const float *part, int chunks, float *stats, hipStream_t s);
 hipError_t launch_attn_colsum_mfma(const Dims &d, const void *q, const void *k, const float *stats, float *a_raw,
+                                   hipStream_t s);
+// the same two sweeps with wave-private key streams (larger groups and windows, d_h = 64); same partial layout
+hipError_t launch_attn_stats_wave(const Dims &d, const void *q, const void *k, float *part, int chunks, hipStream_t s);
+hipError_t launch_attn_colsum_wave(const Dims &d, const void *q, const void *k, const float *stats, float *a_raw,
                                    hipStream_t s);
 // projected-value L1 norm; w_t is [d_model, H*dh]
 hipError_t launch_vproj_generic(const Dims &d, int dtype, const void *v, const void *w_t, float *vnorm,
