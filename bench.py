@@ -316,6 +316,58 @@ class Workload:
         return out
 
 
+def run_probes(P, ev, stream):
+    """What this device sustains for the two resources the pass is priced against (the library's measurement aids):
+    a register-only bf16 MFMA loop in the projection kernel's launch geometry, and plain streaming reads."""
+    import numpy as np
+    import torch
+    sh = stream.cuda_stream or None
+    out = {}
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda")
+    with torch.cuda.stream(stream):
+        rnd = torch.randn(1 << 19, dtype=torch.float32, device="cuda").to(torch.bfloat16)   # 1 MiB of bf16
+        zero = torch.zeros(1 << 19, dtype=torch.bfloat16, device="cuda")
+        for name, ops in (("random_operands", rnd), ("zero_operands", zero)):
+            flop = P.criticalkv_probe_mfma_bf16(ops, 2000, sink, stream=stream)      # warm-up
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(5):
+                e0, e1 = ev.new(), ev.new()
+                ev.record(e0, sh)
+                flop = P.criticalkv_probe_mfma_bf16(ops, 20000, sink, stream=stream)
+                ev.record(e1, sh)
+                torch.cuda.synchronize()
+                ts.append(ev.ms(e0, e1))
+            tf = flop / (float(np.median(ts)) * 1e-3) / 1e12
+            out["mfma_bf16_16x16x32_" + name] = {"tflops": round(tf, 1), "frac_of_2500": round(tf / PEAK_BF16_TFLOPS, 4),
+                                                  "launch_ms": round(float(np.median(ts)), 3)}
+        big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
+        other = torch.empty(1 << 31, dtype=torch.uint8, device="cuda").fill_(5)
+        isink = torch.zeros(16, dtype=torch.int32, device="cuda")
+        for mib in (256, 1024):
+            nbytes = mib << 20
+            res = {}
+            for mode in ("cold", "after_write_elsewhere", "second_read"):
+                ts = []
+                for _ in range(6):
+                    P.criticalkv_probe_hbm_read(other, other.numel(), isink, stream=stream)   # pushes `big` out of the caches
+                    if mode == "after_write_elsewhere":
+                        other[:nbytes].fill_(7)
+                    if mode == "second_read":
+                        P.criticalkv_probe_hbm_read(big, nbytes, isink, stream=stream)
+                    e0, e1 = ev.new(), ev.new()
+                    ev.record(e0, sh)
+                    P.criticalkv_probe_hbm_read(big, nbytes, isink, stream=stream)
+                    ev.record(e1, sh)
+                    torch.cuda.synchronize()
+                    ts.append(ev.ms(e0, e1))
+                ms = float(np.median(ts[1:]))
+                res[mode] = {"ms": round(ms, 4), "tb_per_s": round(nbytes / (ms * 1e-3) / 1e12, 2)}
+            out[f"hbm_read_{mib}MiB"] = res
+        del big, other
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -345,6 +397,10 @@ def main():
     ap.add_argument("--norm", choices=["l1", "l2", "none"], default="l1",
                     help="l1: the paper's default (dense d_model-wide projection); l2: the L2 variant via the Gram "
                          "matrix; none: attention-only baseline selection (no projected magnitude)")
+    ap.add_argument("--probes", action="store_true",
+                    help="also run the library's two measurement aids on this device and report them (probes): a "
+                         "register-only bf16 MFMA loop on random and on zero operands, and streaming reads of 256 MiB "
+                         "and 1 GiB (cold, right after a write of the same size elsewhere, and read a second time)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale profiler byte counters)")
     args = ap.parse_args()
@@ -568,6 +624,10 @@ def main():
         extras_ms["diagnostics_mean_over_heads"] = {name: round(float(dg[..., j].mean()), 5) for name, j in f.items()}
         extras_ms["heads_with_sigma_above_half"] = round(float((dg[..., f["sigma"]] > 0.5).mean()), 4)
 
+    probes = None
+    if args.probes:
+        probes = run_probes(P, ev, stream)
+
     # ---- the GPU side of the parity figures: one pass over input set 0 with the magnitudes kept ---------------
     gpu_out = None
     if with_oracle:
@@ -641,6 +701,8 @@ def main():
         "beside_the_pass_ms": extras_ms,
         "pass_lower_bound_ms": round(t_bound_ms, 4), "pass_frac_of_bound": round(t_bound_ms / ms_per_step, 4),
     }
+    if probes is not None:
+        out["probes"] = probes
     host0 = wl.host0
     # free the main workload's device memory before the other shapes are made resident
     del wl, sets, lanes, lane0, budget, alloc_budget, dev

@@ -293,6 +293,22 @@ CKV_API int criticalkv_compact(const ckv_layer_desc *desc, const void *k, const 
                                const int32_t *count, int32_t max_budget, void *k_out, void *v_out,
                                void *hip_stream);
 
+/*
+ * Measurement aids, no part of the pass: what the device sustains for the two resources the pass is priced against.
+ * Benchmarks report them beside their roofline fractions (the published peaks assume clocks and access patterns
+ * that real data and real kernels do not reach).
+ *   criticalkv_probe_mfma_bf16: a register-only loop of bf16 matrix-core instructions (16x16x32, seven accumulator
+ *     chains per wave, two 4-wave workgroups per CU: the launch geometry of the projection kernel) whose operands
+ *     are taken from `operands` (device, 1 MiB, 16-byte aligned; random values toggle the multipliers as real data
+ *     does, zeros do not).  *flop_out (host, may be NULL) receives the floating-point operations of the launch.
+ *   criticalkv_probe_hbm_read: a plain streaming read of `bytes` bytes at `buf` (device, 16-byte aligned).
+ * `sink` is a device word that is never written (it keeps the work alive).  Both enqueue one kernel on the stream
+ * and return; the caller times them.
+ */
+CKV_API int criticalkv_probe_mfma_bf16(const void *operands, int32_t iters, double *flop_out, float *sink,
+                                       void *hip_stream);
+CKV_API int criticalkv_probe_hbm_read(const void *buf, size_t bytes, uint32_t *sink, void *hip_stream);
+
 /* Static, NUL-terminated description of an error code. */
 CKV_API const char *criticalkv_strerror(int code);
 

@@ -25,7 +25,7 @@ CKV_STATIC_SCRATCH_BYTES = 12 << 20
 EXPORTS = ("criticalkv_workspace_bytes", "criticalkv_score", "criticalkv_score_profiled", "criticalkv_select",
            "criticalkv_compact", "criticalkv_strerror", "criticalkv_gram_bytes", "criticalkv_prepare_gram",
            "criticalkv_allocate", "criticalkv_diagnostics", "criticalkv_select_noalloc", "criticalkv_prepared_wo_bytes",
-           "criticalkv_prepare_wo")
+           "criticalkv_prepare_wo", "criticalkv_probe_mfma_bf16", "criticalkv_probe_hbm_read")
 STAGES = ("wo_layout", "attn_stats", "attn_colsum", "vproj", "combine")
 
 
@@ -98,6 +98,10 @@ def load() -> ctypes.CDLL:
         lib.criticalkv_prepared_wo_bytes.argtypes = [dp]
         lib.criticalkv_prepare_wo.restype = ctypes.c_int
         lib.criticalkv_prepare_wo.argtypes = [dp, vp, vp, vp]
+        lib.criticalkv_probe_mfma_bf16.restype = ctypes.c_int
+        lib.criticalkv_probe_mfma_bf16.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), vp, vp]
+        lib.criticalkv_probe_hbm_read.restype = ctypes.c_int
+        lib.criticalkv_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         lib.criticalkv_allocate.restype = ctypes.c_int
         lib.criticalkv_allocate.argtypes = [dp, vp, i32, f32, vp, vp, ctypes.c_size_t, vp]
         lib.criticalkv_diagnostics.restype = ctypes.c_int
@@ -203,6 +207,21 @@ def criticalkv_allocate(desc: LayerDesc, attn, total_budget: int, floor_frac: fl
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != CKV_OK:
         raise CriticalKVError(rc, "criticalkv_allocate")
+
+
+def criticalkv_probe_mfma_bf16(operands, iters: int, sink, *, stream=None) -> float:
+    """Enqueues the register-only bf16 MFMA loop; returns the launch's floating-point operation count."""
+    flop = ctypes.c_double()
+    rc = load().criticalkv_probe_mfma_bf16(_ptr(operands), int(iters), ctypes.byref(flop), _ptr(sink), _stream(stream))
+    if rc != CKV_OK:
+        raise CriticalKVError(rc, "criticalkv_probe_mfma_bf16")
+    return float(flop.value)
+
+
+def criticalkv_probe_hbm_read(buf, nbytes: int, sink, *, stream=None) -> None:
+    rc = load().criticalkv_probe_hbm_read(_ptr(buf), int(nbytes), _ptr(sink), _stream(stream))
+    if rc != CKV_OK:
+        raise CriticalKVError(rc, "criticalkv_probe_hbm_read")
 
 
 DIAG_FIELDS = ("sigma", "s", "C", "theta", "theta_hat", "theta_relax", "L", "M")

@@ -61,7 +61,7 @@ static int resolve(const ckv_layer_desc *desc, Dims *out)
     return CKV_OK;
 }
 
-Workspace carve_workspace(const Dims &d, int dtype, bool need_wt, int max_budget)
+Workspace carve_workspace(const Dims &d, int dtype, int max_budget)
 {
     Workspace w;
     size_t off = 0;
@@ -71,7 +71,8 @@ Workspace carve_workspace(const Dims &d, int dtype, bool need_wt, int max_budget
     w.vnorm = off; off = align256(off + per_head * 4);
     w.stats_part = off; off = align256(off + (size_t)d.batch * d.H * d.W * w.max_chunks * 2 * 4);
     w.stats = off; off = align256(off + (size_t)d.batch * d.H * d.W * 2 * 4);
-    w.w_t = off; if (need_wt) off = align256(off + (size_t)d.H * d.dh * d.dm * elem_size(dtype));
+    // (reserved whether or not this call re-lays the projection out: every call on a layer sees the same offsets)
+    w.w_t = off; off = align256(off + (size_t)d.H * d.dh * d.dm * elem_size(dtype));
     w.l2_scratch = off; if (d.norm == CKV_NORM_L2 && d.dh == 128) off = align256(off + vproj_l2_workspace_bytes(d));
     w.sel_keys = off; off = align256(off + (size_t)d.batch * d.Hkv * d.n * 4);
     w.sel_scratch = off; off = align256(off + select_workspace_words(d.batch * d.Hkv, d.n) * 4);
@@ -128,7 +129,7 @@ size_t criticalkv_workspace_bytes(const ckv_layer_desc *desc, int32_t max_budget
     if (resolve(desc, &d) != CKV_OK || max_budget < 0) return 0;
     // sized for either w_o layout and either norm so that one allocation serves every call on this layer
     d.norm = CKV_NORM_L2;
-    return carve_workspace(d, desc->dtype, true, max_budget).total;
+    return carve_workspace(d, desc->dtype, max_budget).total;
 }
 
 static void mark(void *const *ev, int slot, hipStream_t s)
@@ -136,88 +137,129 @@ static void mark(void *const *ev, int slot, hipStream_t s)
     if (ev && ev[slot]) (void)hipEventRecord((hipEvent_t)ev[slot], s);
 }
 
+// What a score call works with once its arguments are validated: sizes, the carved workspace, the kernels chosen.
+struct ScorePlan {
+    Dims d;
+    Workspace ws;
+    char *base;
+    float *a_raw, *vnorm, *part, *stats;
+    const void *w_t; // the projection in output-major layout (the caller's, or the workspace copy)
+    bool attn_only, have_gram, need_wt, tile_a, wave_a, mfma_v, l2_mfma;
+    int chunks;
+    hipStream_t s;
+};
+
+// Validation and workspace carving of criticalkv_score.  No HIP call.
+static int score_plan(const ckv_layer_desc *desc, const void *q_win, const void *k, const void *v, const void *w_o,
+                      float *attn, float *crit, float *vnorm_opt, void *workspace, size_t workspace_bytes,
+                      void *hip_stream, ScorePlan *out)
+{
+    ScorePlan p;
+    int rc = resolve(desc, &p.d);
+    if (rc != CKV_OK) return rc;
+    const Dims &d = p.d;
+    p.attn_only = desc->flags & CKV_ATTN_ONLY;
+    if (!q_win || !k || !attn || !crit || (!p.attn_only && (!v || !w_o))) return CKV_E_INVALID_ARG;
+    if (p.attn_only && vnorm_opt) return CKV_E_INVALID_ARG; // no magnitudes are computed in this mode
+    if (misaligned16(q_win) || misaligned16(k) || misaligned16(v) || misaligned16(w_o) || misaligned16(attn) ||
+        misaligned16(crit) || misaligned16(vnorm_opt))
+        return CKV_E_INVALID_ARG;
+    p.have_gram = desc->flags & CKV_WO_IS_GRAM;
+    if (p.have_gram && !(mfma_allowed(desc) && vproj_l2_mfma_supported(d))) return CKV_E_UNSUPPORTED;
+    p.need_wt = !p.attn_only && !p.have_gram && !(desc->flags & CKV_WO_OUT_IN);
+    p.ws = carve_workspace(d, desc->dtype, 0);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < p.ws.total) return CKV_E_WORKSPACE;
+    p.s = (hipStream_t)hip_stream;
+    p.base = (char *)workspace;
+    p.a_raw = (float *)(p.base + p.ws.a_raw);
+    p.vnorm = p.attn_only ? nullptr : vnorm_opt ? vnorm_opt : (float *)(p.base + p.ws.vnorm);
+    p.part = (float *)(p.base + p.ws.stats_part);
+    p.stats = (float *)(p.base + p.ws.stats);
+    p.w_t = p.need_wt ? (const void *)(p.base + p.ws.w_t) : w_o;
+    // matrix-core attention: one wave per query head over shared key tiles where a kv group has at most four
+    // 32-row blocks of window queries (the 4:1 group with a 32-row window), wave-private key streams otherwise
+    const int row_blocks = d.G * ((d.W + 31) / 32);
+    p.tile_a = mfma_allowed(desc) && attn_mfma_supported(d) && (row_blocks <= 4 || !attn_wave_supported(d));
+    p.wave_a = mfma_allowed(desc) && !p.tile_a && attn_wave_supported(d);
+    p.mfma_v = mfma_allowed(desc) && vproj_mfma_supported(d);
+    p.l2_mfma = d.norm == CKV_NORM_L2 && mfma_allowed(desc) && vproj_l2_mfma_supported(d);
+    p.chunks = p.tile_a ? mfma_attn_chunks(d) : p.wave_a ? wave_attn_chunks(d) : generic_attn_chunks(d);
+    if (p.chunks > p.ws.max_chunks) return CKV_E_WORKSPACE;
+    *out = p;
+    return CKV_OK;
+}
+
+// Layout change of a canonical W_O and the two key sweeps: a_raw (per query head, before pooling).
+static int score_attention(const ScorePlan &p, const ckv_layer_desc *desc, const void *q_win, const void *k,
+                           const void *w_o, void *const *ev)
+{
+    const Dims &d = p.d;
+    hipStream_t s = p.s;
+    hipError_t e;
+    mark(ev, 2 * CKV_STAGE_WO_LAYOUT, s);
+    if (p.need_wt) {
+        e = launch_transpose_wo(d, desc->dtype, w_o, p.base + p.ws.w_t, s);
+        if (e != hipSuccess) return CKV_E_HIP;
+    }
+    mark(ev, 2 * CKV_STAGE_WO_LAYOUT + 1, s);
+    mark(ev, 2 * CKV_STAGE_ATTN_STATS, s);
+    e = p.tile_a ? launch_attn_stats_mfma(d, q_win, k, p.part, p.chunks, s)
+        : p.wave_a ? launch_attn_stats_wave(d, q_win, k, p.part, p.chunks, s)
+                   : launch_attn_stats_generic(d, desc->dtype, q_win, k, p.part, p.chunks, s);
+    if (e != hipSuccess) return CKV_E_HIP;
+    e = (p.tile_a || p.wave_a) ? launch_attn_stats_reduce_log2(d, p.part, p.chunks, p.stats, s)
+                               : launch_attn_stats_reduce(d, p.part, p.chunks, p.stats, s);
+    if (e != hipSuccess) return CKV_E_HIP;
+    mark(ev, 2 * CKV_STAGE_ATTN_STATS + 1, s);
+    mark(ev, 2 * CKV_STAGE_ATTN_COLSUM, s);
+    e = p.tile_a ? launch_attn_colsum_mfma(d, q_win, k, p.stats, p.a_raw, s)
+        : p.wave_a ? launch_attn_colsum_wave(d, q_win, k, p.stats, p.a_raw, s)
+                   : launch_attn_colsum_generic(d, desc->dtype, q_win, k, p.stats, p.a_raw, s);
+    if (e != hipSuccess) return CKV_E_HIP;
+    mark(ev, 2 * CKV_STAGE_ATTN_COLSUM + 1, s);
+    return CKV_OK;
+}
+
+// The projected-value magnitudes (nothing in the attention-only mode).
+static int score_magnitudes(const ScorePlan &p, const ckv_layer_desc *desc, const void *v, const void *w_o, void *const *ev)
+{
+    const Dims &d = p.d;
+    hipStream_t s = p.s;
+    hipError_t e = hipSuccess;
+    mark(ev, 2 * CKV_STAGE_VPROJ, s);
+    if (p.attn_only) {
+        // combine then writes crit = attn
+    } else if (p.l2_mfma) {
+        const void *gram = w_o; // prepared by the caller, or computed here from the projection
+        if (!p.have_gram) {
+            char *scratch = p.base + p.ws.l2_scratch;
+            void *g = scratch + vproj_l2_workspace_bytes(d) - vproj_l2_gram_bytes(d);
+            e = launch_gram(d, p.w_t, g, scratch, s);
+            if (e != hipSuccess) return CKV_E_HIP;
+            gram = g;
+        }
+        e = launch_vproj_l2_mfma(d, v, gram, p.vnorm, s);
+    } else if (d.norm == CKV_NORM_L1 && p.mfma_v)
+        e = launch_vproj_mfma(d, v, p.w_t, p.vnorm, s);
+    else
+        e = launch_vproj_generic(d, desc->dtype, v, p.w_t, p.vnorm, s);
+    if (e != hipSuccess) return CKV_E_HIP;
+    mark(ev, 2 * CKV_STAGE_VPROJ + 1, s);
+    return CKV_OK;
+}
+
 static int score_impl(const ckv_layer_desc *desc, const void *q_win, const void *k, const void *v, const void *w_o,
                       float *attn, float *crit, float *vnorm_opt, void *workspace, size_t workspace_bytes,
                       void *hip_stream, void *const *ev)
 {
-    Dims d;
-    int rc = resolve(desc, &d);
+    ScorePlan p;
+    int rc = score_plan(desc, q_win, k, v, w_o, attn, crit, vnorm_opt, workspace, workspace_bytes, hip_stream, &p);
     if (rc != CKV_OK) return rc;
-    const bool attn_only = desc->flags & CKV_ATTN_ONLY;
-    if (!q_win || !k || !attn || !crit || (!attn_only && (!v || !w_o))) return CKV_E_INVALID_ARG;
-    if (attn_only && vnorm_opt) return CKV_E_INVALID_ARG; // no magnitudes are computed in this mode
-    if (misaligned16(q_win) || misaligned16(k) || misaligned16(v) || misaligned16(w_o) || misaligned16(attn) ||
-        misaligned16(crit) || misaligned16(vnorm_opt))
-        return CKV_E_INVALID_ARG;
-    const bool have_gram = desc->flags & CKV_WO_IS_GRAM;
-    if (have_gram && !(mfma_allowed(desc) && vproj_l2_mfma_supported(d))) return CKV_E_UNSUPPORTED;
-    const bool need_wt = !attn_only && !have_gram && !(desc->flags & CKV_WO_OUT_IN);
-    const Workspace ws = carve_workspace(d, desc->dtype, need_wt, 0);
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
-
-    hipStream_t s = (hipStream_t)hip_stream;
-    char *base = (char *)workspace;
-    float *a_raw = (float *)(base + ws.a_raw);
-    float *vnorm = vnorm_opt ? vnorm_opt : (float *)(base + ws.vnorm);
-    float *part = (float *)(base + ws.stats_part);
-    float *stats = (float *)(base + ws.stats);
-    const void *w_t = w_o;
-    hipError_t e;
-    mark(ev, 2 * CKV_STAGE_WO_LAYOUT, s);
-    if (need_wt) {
-        e = launch_transpose_wo(d, desc->dtype, w_o, base + ws.w_t, s);
-        if (e != hipSuccess) return CKV_E_HIP;
-        w_t = base + ws.w_t;
-    }
-    mark(ev, 2 * CKV_STAGE_WO_LAYOUT + 1, s);
-    // matrix-core attention: one wave per query head over shared key tiles where a kv group has at most four
-    // 32-row blocks of window queries (the 4:1 group with a 32-row window), wave-private key streams otherwise
-    const int row_blocks = d.G * ((d.W + 31) / 32);
-    const bool tile_a = mfma_allowed(desc) && attn_mfma_supported(d) && (row_blocks <= 4 || !attn_wave_supported(d));
-    const bool wave_a = mfma_allowed(desc) && !tile_a && attn_wave_supported(d);
-    const bool mfma_v = mfma_allowed(desc) && vproj_mfma_supported(d);
-    const int chunks = tile_a ? mfma_attn_chunks(d) : wave_a ? wave_attn_chunks(d) : generic_attn_chunks(d);
-    if (chunks > ws.max_chunks) return CKV_E_WORKSPACE;
-
-    mark(ev, 2 * CKV_STAGE_ATTN_STATS, s);
-    e = tile_a ? launch_attn_stats_mfma(d, q_win, k, part, chunks, s)
-        : wave_a ? launch_attn_stats_wave(d, q_win, k, part, chunks, s)
-                 : launch_attn_stats_generic(d, desc->dtype, q_win, k, part, chunks, s);
-    if (e != hipSuccess) return CKV_E_HIP;
-    e = (tile_a || wave_a) ? launch_attn_stats_reduce_log2(d, part, chunks, stats, s)
-                           : launch_attn_stats_reduce(d, part, chunks, stats, s);
-    if (e != hipSuccess) return CKV_E_HIP;
-    mark(ev, 2 * CKV_STAGE_ATTN_STATS + 1, s);
-    mark(ev, 2 * CKV_STAGE_ATTN_COLSUM, s);
-    e = tile_a ? launch_attn_colsum_mfma(d, q_win, k, stats, a_raw, s)
-        : wave_a ? launch_attn_colsum_wave(d, q_win, k, stats, a_raw, s)
-                 : launch_attn_colsum_generic(d, desc->dtype, q_win, k, stats, a_raw, s);
-    if (e != hipSuccess) return CKV_E_HIP;
-    mark(ev, 2 * CKV_STAGE_ATTN_COLSUM + 1, s);
-    mark(ev, 2 * CKV_STAGE_VPROJ, s);
-    if (attn_only) {
-        e = hipSuccess;
-        vnorm = nullptr; // combine then writes crit = attn
-    } else if (d.norm == CKV_NORM_L2 && mfma_allowed(desc) && vproj_l2_mfma_supported(d)) {
-        const void *gram = w_o; // prepared by the caller, or computed here from the projection
-        if (!have_gram) {
-            char *scratch = base + ws.l2_scratch;
-            void *g = scratch + vproj_l2_workspace_bytes(d) - vproj_l2_gram_bytes(d);
-            e = launch_gram(d, w_t, g, scratch, s);
-            if (e != hipSuccess) return CKV_E_HIP;
-            gram = g;
-        }
-        e = launch_vproj_l2_mfma(d, v, gram, vnorm, s);
-    } else if (d.norm == CKV_NORM_L1 && mfma_v)
-        e = launch_vproj_mfma(d, v, w_t, vnorm, s);
-    else
-        e = launch_vproj_generic(d, desc->dtype, v, w_t, vnorm, s);
-    if (e != hipSuccess) return CKV_E_HIP;
-    mark(ev, 2 * CKV_STAGE_VPROJ + 1, s);
-    mark(ev, 2 * CKV_STAGE_COMBINE, s);
-    e = launch_combine(d, a_raw, vnorm, attn, crit, s);
-    if (e != hipSuccess) return CKV_E_HIP;
-    mark(ev, 2 * CKV_STAGE_COMBINE + 1, s);
+    if ((rc = score_attention(p, desc, q_win, k, w_o, ev)) != CKV_OK) return rc;
+    if ((rc = score_magnitudes(p, desc, v, w_o, ev)) != CKV_OK) return rc;
+    mark(ev, 2 * CKV_STAGE_COMBINE, p.s);
+    if (launch_combine(p.d, p.a_raw, p.vnorm, attn, crit, p.s) != hipSuccess) return CKV_E_HIP;
+    mark(ev, 2 * CKV_STAGE_COMBINE + 1, p.s);
     return CKV_OK;
 }
 
@@ -254,7 +296,7 @@ int criticalkv_prepare_gram(const ckv_layer_desc *desc, const void *w_o, void *g
     if (desc->dtype != CKV_BF16 || !vproj_l2_mfma_supported(d)) return CKV_E_UNSUPPORTED;
     d.norm = CKV_NORM_L2; // the carve below must contain the Gram scratch whatever norm the descriptor names
     const bool need_wt = !(desc->flags & CKV_WO_OUT_IN);
-    const Workspace ws = carve_workspace(d, desc->dtype, need_wt, 0);
+    const Workspace ws = carve_workspace(d, desc->dtype, 0);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     char *base = (char *)workspace;
@@ -277,7 +319,7 @@ int criticalkv_select(const ckv_layer_desc *desc, const float *attn, const float
     if (misaligned16(attn) || misaligned16(crit)) return CKV_E_INVALID_ARG;
     if (!(alpha >= 0.0f) || !(alpha <= 1.0f)) return CKV_E_INVALID_ARG;
     if (max_budget < 1 || max_budget > d.n) return CKV_E_INVALID_ARG;
-    const Workspace ws = carve_workspace(d, desc->dtype, false, 0);
+    const Workspace ws = carve_workspace(d, desc->dtype, 0);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
     uint32_t *keys2 = (uint32_t *)((char *)workspace + ws.sel_keys);
     uint32_t *scratch = (uint32_t *)((char *)workspace + ws.sel_scratch);
@@ -339,7 +381,7 @@ int criticalkv_allocate(const ckv_layer_desc *desc, const float *attn, int32_t t
     const int floor_each = (int)floor((double)floor_frac * (double)total_budget / (double)d.Hkv);
     const int64_t pool = std::min<int64_t>((int64_t)total_budget - (int64_t)d.Hkv * floor_each, (int64_t)d.Hkv * d.n);
     const int per_head = (int)((pool + d.Hkv - 1) / d.Hkv);
-    const Workspace ws = carve_workspace(d, desc->dtype, false, per_head);
+    const Workspace ws = carve_workspace(d, desc->dtype, per_head);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
     uint32_t *keys2 = (uint32_t *)((char *)workspace + ws.sel_keys);
     uint32_t *scratch = (uint32_t *)((char *)workspace + ws.sel_scratch);
@@ -359,7 +401,7 @@ int criticalkv_diagnostics(const ckv_layer_desc *desc, const void *v, const void
     if (misaligned16(v) || misaligned16(w_o) || misaligned16(vnorm_opt)) return CKV_E_INVALID_ARG;
     if (desc->flags & (CKV_ATTN_ONLY | CKV_WO_IS_GRAM)) return CKV_E_INVALID_ARG; // needs the magnitudes and W_O itself
     if (max_budget < 1 || max_budget > d.n) return CKV_E_INVALID_ARG;
-    const Workspace ws = carve_workspace(d, desc->dtype, false, 0); // the layout criticalkv_select used
+    const Workspace ws = carve_workspace(d, desc->dtype, 0); // the layout criticalkv_select used
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return CKV_E_WORKSPACE;
     char *base = (char *)workspace;
     const float *vnorm = vnorm_opt ? vnorm_opt : (const float *)(base + ws.vnorm);

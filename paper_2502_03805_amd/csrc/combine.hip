@@ -4,6 +4,7 @@
 //   abar^h_i = max{ a^h_j : |j - i| <= pool_k/2, 0 <= j < n }
 //   attn[g,i] = (1/G) sum_{h in g} abar^h_i
 //   crit[g,i] = (1/G) sum_{h in g} (abar^h_i + eps) * N^h_i      (= attn[g,i] when no magnitudes are given)
+// Either output pointer may be null (that array is then not written).
 // Every output is computed by the same sequence of fp32 operations on its inputs, so
 // entries whose pooled scores are equal get bitwise equal keys (ties stay ties).
 #include "common.hpp"
@@ -65,8 +66,8 @@ __global__ __launch_bounds__(CB_THREADS) void combine_kernel(const float *__rest
     }
     if (i < n) {
         const size_t o = ((size_t)bi * Hkv + g) * (size_t)n + i;
-        attn[o] = sum_a / (float)G;
-        crit[o] = sum_c / (float)G;
+        if (attn) attn[o] = sum_a / (float)G;
+        if (crit) crit[o] = sum_c / (float)G;
     }
 }
 

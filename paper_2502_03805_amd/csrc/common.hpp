@@ -51,7 +51,7 @@ bool attn_wave_supported(const Dims &d);  // shapes the wave-private matrix-core
 int wave_attn_chunks(const Dims &d);
 bool vproj_mfma_supported(const Dims &d); // shapes the matrix-core projection kernel covers
 
-Workspace carve_workspace(const Dims &d, int dtype, bool need_wt, int max_budget);
+Workspace carve_workspace(const Dims &d, int dtype, int max_budget);
 
 // ---- kernel launchers (each returns hipGetLastError after its launches) -------------------------
 // window attention, pass 1: per (row, key chunk) running max and sum of exp
@@ -85,13 +85,20 @@ hipError_t launch_gram(const Dims &d, const void *w_t, void *gram_out, void *par
 hipError_t launch_vproj_l2_mfma(const Dims &d, const void *v, const void *gram, float *vnorm, hipStream_t s);
 // [H*dh, d_model] -> [d_model, H*dh]
 hipError_t launch_transpose_wo(const Dims &d, int dtype, const void *w_o, void *w_t, hipStream_t s);
-// pool + eps + product + group mean
+// pool + eps + product + group mean; crit may be null (only the pooled attention is written)
 hipError_t launch_combine(const Dims &d, const float *a_raw, const float *vnorm, float *attn, float *crit,
                           hipStream_t s);
 size_t select_workspace_words(int heads, int n); // u32 words of histogram / state / per-slice scratch
 hipError_t launch_select(const Dims &d, const float *attn, const float *crit, const int32_t *budget, float alpha,
                          int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2, uint32_t *scratch,
                          hipStream_t s);
+// the selection in two halves: stage 1's digit histograms need attn only (they can run beside the projection),
+// the rest needs crit as well
+hipError_t launch_select_stage1_hist(int heads, int n, int protect, const float *attn, const int32_t *budget, float alpha,
+                                     int max_budget, uint32_t *keys2, uint32_t *scratch, hipStream_t s);
+hipError_t launch_select_finish(int heads, int n, int protect, const float *attn, const float *crit, const int32_t *budget,
+                                float alpha, int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2,
+                                uint32_t *scratch, hipStream_t s);
 // per-head budgets from a per-batch-item total; tmp holds 2 * batch + batch * total int32
 hipError_t launch_allocate(const Dims &d, const float *attn, int total, float floor_frac, int32_t *budget_out,
                            uint32_t *keys2, uint32_t *scratch, int32_t *tmp, hipStream_t s);

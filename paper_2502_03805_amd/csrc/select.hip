@@ -420,10 +420,8 @@ size_t select_workspace_words(int heads, int n)
     return (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS) + (size_t)heads * 3 * n_slices + (size_t)heads * n_slices * (1024 + 1025);
 }
 
-// heads rows of n keys each (a row is one (batch item, kv head), or one whole batch item for the allocation)
-hipError_t launch_select_rows(int heads, int n, int protect, const float *attn, const float *crit,
-                              const int32_t *budget, float alpha, int max_budget, int32_t *idx, int32_t *count,
-                              uint32_t *keys2, uint32_t *scratch, hipStream_t s)
+static SelArgs make_sel_args(int heads, int n, int protect, const float *attn, const float *crit, const int32_t *budget,
+                             float alpha, int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2, uint32_t *scratch)
 {
     SelArgs A;
     A.attn = reinterpret_cast<const uint32_t *>(attn);
@@ -440,17 +438,46 @@ hipError_t launch_select_rows(int heads, int n, int protect, const float *attn, 
     A.n_slices = (n + SEL_SLICE - 1) / SEL_SLICE;
     A.slice_hist = A.slices + (size_t)heads * 3 * A.n_slices;
     A.slice_suf = A.slice_hist + (size_t)heads * A.n_slices * 1024;
+    return A;
+}
+
+// First half of the selection: the three digit histograms of stage 1.  It reads attn only (not crit), so it can
+// run while the projected-value magnitudes are still being computed.
+hipError_t launch_select_stage1_hist(int heads, int n, int protect, const float *attn, const int32_t *budget, float alpha,
+                                     int max_budget, uint32_t *keys2, uint32_t *scratch, hipStream_t s)
+{
+    const SelArgs A = make_sel_args(heads, n, protect, attn, attn, budget, alpha, max_budget, nullptr, nullptr, keys2, scratch);
     const size_t zero_words = (size_t)heads * (2 * 3 * SEL_BINS + 2 * ST_WORDS);
     dim3 grid(A.n_slices, heads), block(SEL_THREADS);
     hipLaunchKernelGGL(select_zero_kernel, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, s, scratch, zero_words);
     hipLaunchKernelGGL((select_hist_kernel<0, 0>), grid, block, 0, s, A);
     hipLaunchKernelGGL((select_hist_kernel<0, 1>), grid, block, 0, s, A);
     hipLaunchKernelGGL((select_hist_kernel<0, 2>), grid, block, 0, s, A);
+    return hipGetLastError();
+}
+
+// Second half: stage-1 membership and stage-2 keys, the two remaining histograms of stage 2, the ordered write.
+hipError_t launch_select_finish(int heads, int n, int protect, const float *attn, const float *crit, const int32_t *budget,
+                                float alpha, int max_budget, int32_t *idx, int32_t *count, uint32_t *keys2,
+                                uint32_t *scratch, hipStream_t s)
+{
+    const SelArgs A = make_sel_args(heads, n, protect, attn, crit, budget, alpha, max_budget, idx, count, keys2, scratch);
+    dim3 grid(A.n_slices, heads), block(SEL_THREADS);
     hipLaunchKernelGGL(select_mark_kernel, grid, block, 0, s, A);
     hipLaunchKernelGGL((select_hist_kernel<1, 1>), grid, block, 0, s, A);
     hipLaunchKernelGGL((select_hist_kernel<1, 2>), grid, block, 0, s, A);
     hipLaunchKernelGGL(select_write_kernel, grid, block, 0, s, A);
     return hipGetLastError();
+}
+
+// heads rows of n keys each (a row is one (batch item, kv head), or one whole batch item for the allocation)
+hipError_t launch_select_rows(int heads, int n, int protect, const float *attn, const float *crit,
+                              const int32_t *budget, float alpha, int max_budget, int32_t *idx, int32_t *count,
+                              uint32_t *keys2, uint32_t *scratch, hipStream_t s)
+{
+    hipError_t e = launch_select_stage1_hist(heads, n, protect, attn, budget, alpha, max_budget, keys2, scratch, s);
+    if (e != hipSuccess) return e;
+    return launch_select_finish(heads, n, protect, attn, crit, budget, alpha, max_budget, idx, count, keys2, scratch, s);
 }
 
 hipError_t launch_select(const Dims &d, const float *attn, const float *crit, const int32_t *budget, float alpha,

@@ -798,6 +798,42 @@ def test_pass_replays_from_a_hip_graph(P):
     compare_selection(replayed["idx"].cpu().numpy(), replayed["count"].cpu().numpy(), ref, B, cfg.alpha)
 
 
+def test_prepared_projection_layout_matches_the_per_call_one(P):
+    """criticalkv_prepare_wo once, then criticalkv_score with CKV_WO_OUT_IN on the prepared copy: bit for bit the
+    scores that criticalkv_score gives when it is handed the canonical projection and re-lays it out itself."""
+    import torch
+    for cfg in (reduced(CONFIGS["llama32k"], 2100, d_model=1024), CONFIGS["tiny"]):
+        t = make_layer(cfg)
+        canon = cfg_desc(P, cfg)
+        dev = to_device(cfg, t, False)
+        prepared = torch.empty(P.prepared_wo_bytes(canon), dtype=torch.uint8, device="cuda")
+        P.criticalkv_prepare_wo(canon, dev["w_o"], prepared)
+        torch.cuda.synchronize()
+        assert torch.equal(prepared.view(dev["w_o"].dtype).view(cfg.d_model, -1), dev["w_o"].t().contiguous())
+        per_call = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, wo_out_in=False)
+        dev2 = dict(dev, w_o=prepared)
+        once = run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, flags=P.CKV_WO_OUT_IN, dev=dev2)
+        for name in ("attn", "crit", "vnorm", "idx"):
+            assert np.array_equal(getattr(per_call, name), getattr(once, name)), name
+
+
+def test_measurement_probes_run(P):
+    """The two measurement aids enqueue one kernel each and report plausible work (no timing asserted here)."""
+    import torch
+    ops = torch.randn(1 << 19, dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda")
+    flop = P.criticalkv_probe_mfma_bf16(ops, 10, sink)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert flop == 2 * cus * 4 * 10 * (4 * 4 * 7) * 2 * 16 * 16 * 32
+    buf = torch.zeros(1 << 24, dtype=torch.uint8, device="cuda")
+    isink = torch.zeros(16, dtype=torch.int32, device="cuda")
+    P.criticalkv_probe_hbm_read(buf, buf.numel(), isink)
+    torch.cuda.synchronize()
+    assert float(sink.abs().sum()) == 0.0 and int(isink.abs().sum()) == 0
+    with pytest.raises(P.CriticalKVError):
+        P.criticalkv_probe_mfma_bf16(ops, 0, sink)
+
+
 def test_single_hip_runtime_and_side_stream(P):
     """The library must run in PyTorch's HIP runtime (one libamdhip64 mapped) and honour a non-default stream."""
     import torch
