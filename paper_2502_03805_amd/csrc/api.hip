@@ -32,7 +32,6 @@ static int resolve(const ckv_layer_desc *desc, Dims *out)
     if (c.d_model % 32) return CKV_E_UNSUPPORTED;
     if (c.norm != CKV_NORM_L1 && c.norm != CKV_NORM_L2) return CKV_E_INVALID_ARG;
     if (c.pool_kernel > 63) return CKV_E_UNSUPPORTED;
-    if ((int64_t)c.window * c.head_dim > 12288) return CKV_E_UNSUPPORTED; // window queries are staged in LDS
     // index arithmetic inside the kernels is 64-bit for tensors and 32-bit for per-head token indices
     if ((int64_t)c.batch * c.n_q_heads * c.window > (int64_t)1 << 24) return CKV_E_UNSUPPORTED;
     if ((int64_t)c.batch * c.n_q_heads > 65535) return CKV_E_UNSUPPORTED;

@@ -5,7 +5,7 @@
 // only needed as a row-wise sum of magnitudes, so the products live in MFMA accumulators, are
 // folded into per-row partial sums by the epilogue and never reach memory.
 //
-// Tiling (d_h = 128):
+// Tiling (written for d_h = 128; d_h = 64 runs the same kernel with two k-steps per chain and 256-column tiles):
 //   * workgroup = 4 waves, two workgroups per CU; wave w owns RB blocks of 16 token rows whose V
 //     fragments (4 k-steps of 32) stay in registers for the whole kernel: V is read once per
 //     workgroup.  The product is taken transposed, (W_O^h)^T V^T: the streamed W_O fragment is the
@@ -35,24 +35,32 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int VM_THREADS = 256;
 constexpr int VM_WAVES = 4;
-constexpr int VM_DH = 128;
-constexpr int VM_KS = VM_DH / 32;          // k-steps of one 16x16x32 MFMA chain
-constexpr int VM_TN = 128;                 // W_O columns per LDS tile
-constexpr int VM_COL_BYTES = VM_DH * 2;    // 256 B per column, 16 chunks of 16 B
-constexpr int VM_TILE_BYTES = VM_TN * VM_COL_BYTES;
-constexpr int VM_CB = VM_TN / 16;          // 16-column blocks per tile
+constexpr int VM_TILE_BYTES = 32768;       // one LDS tile of W_O columns
 constexpr int VM_LOADS = VM_TILE_BYTES / 1024 / VM_WAVES; // direct loads per wave per tile
+
+template <int DH>
+struct VGeo {
+    static constexpr int KS = DH / 32;                 // k-steps of one 16x16x32 MFMA chain
+    static constexpr int COL_BYTES = DH * 2;           // one W_O column of the head: 16 or 8 chunks of 16 B
+    static constexpr int CPR = COL_BYTES / 16;         // chunks per column
+    static constexpr int TN = VM_TILE_BYTES / COL_BYTES; // W_O columns per LDS tile (128 or 256)
+    static constexpr int CB = TN / 16;                 // 16-column blocks per tile
+    static constexpr int CPK = 1024 / COL_BYTES;       // columns per KiB (one direct load of a wave)
+    static constexpr int LPC = KS / 2;                 // direct loads issued per column block (first half of a tile)
+};
 
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
-template <int RB>
+template <int DH, int RB>
 __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t *__restrict__ v,
                                                                    const bf16_t *__restrict__ w_t,
                                                                    float *__restrict__ vnorm, int H, int G, int n,
                                                                    int dm, int64_t vs0, int64_t vs1, int64_t vs2,
                                                                    int row_tiles, int heads, int pair)
 {
-    static_assert(VM_LOADS == VM_CB, "one direct load per wave and column block");
+    using geo = VGeo<DH>;
+    constexpr int VM_KS = geo::KS, VM_CB = geo::CB, VM_TN = geo::TN, VM_COL_BYTES = geo::COL_BYTES, VM_DH = DH;
+    static_assert(VM_LOADS * 2 == VM_CB * geo::LPC, "the next tile's loads go out during the first half of a tile");
     __shared__ __attribute__((aligned(1024))) char lds[2 * VM_TILE_BYTES];
     // XCD-aware work mapping.  Workgroups of a 1-D grid are handed to the 8 XCDs round-robin (workgroup L
     // runs on XCD L % 8) and every XCD has its own 4 MiB L2.  An XCD gets consecutive (batch item, query head)
@@ -93,20 +101,21 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
 #pragma unroll
         for (int j = 0; j < 4; ++j) sum[rb][j] = 0.f;
 
-    // Direct loads: instruction j of wave w fills LDS KiB m = j * 4 + w of the tile = columns 4m .. 4m+3;
-    // lane i writes slot i % 16 of column 4m + i / 16 and therefore fetches chunk (i % 16) ^ (column & 15).
+    // Direct loads: instruction j of wave w fills LDS KiB m = j * 4 + w of the tile = columns CPK*m .. (CPK = 4 at
+    // d_h 128); lane i writes slot i % CPR of column CPK*m + i / CPR and therefore fetches chunk
+    // (i % CPR) ^ (column & (CPR-1)).
     // They are buffer loads (not flat/global ones): the compiler then keeps exact LDS wait counts.
     const size_t ldw = (size_t)H * VM_DH; // elements between consecutive output columns
-    const int ld_col = wave * 4 + (lane >> 4);                       // column of this lane for j = 0
-    const uint32_t ld_voff =
-        (uint32_t)(((size_t)h * VM_DH + (size_t)ld_col * ldw + (size_t)(((lane & 15) ^ (ld_col & 15)) * 8)) * 2);
-    // (columns advance by 16 per instruction, which leaves column & 15 and thus the chunk unchanged)
+    const int ld_col = wave * geo::CPK + lane / geo::CPR;                // column of this lane for j = 0
+    const uint32_t ld_voff = (uint32_t)(((size_t)h * VM_DH + (size_t)ld_col * ldw +
+                                         (size_t)(((lane % geo::CPR) ^ (ld_col & (geo::CPR - 1))) * 8)) * 2);
+    // (columns advance by 4 * CPK per instruction, a multiple of CPR, which leaves the chunk unchanged)
     const int tiles = dm / VM_TN; // host guarantees dm % VM_TN == 0 and the whole matrix < 2 GiB
     const __amdgpu_buffer_rsrc_t w_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)w_t, 0, (int)((size_t)dm * ldw * 2), 0x00020000);
 
     auto issue_load = [&](int tile, int j, char *buf) {
-        const uint32_t soff = (uint32_t)(((size_t)tile * VM_TN + (size_t)j * 16) * ldw * 2);
+        const uint32_t soff = (uint32_t)(((size_t)tile * VM_TN + (size_t)j * 4 * geo::CPK) * ldw * 2);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, LDS_PTR(buf + (j * 4 + wave) * 1024), 16, ld_voff, soff, 0, 0);
     };
 
@@ -116,7 +125,7 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
     // per-lane byte offsets of the 4 W_O fragments inside a 16-column block
     int boff[VM_KS];
 #pragma unroll
-    for (int s = 0; s < VM_KS; ++s) boff[s] = l16 * VM_COL_BYTES + (((4 * s + kc) ^ l16) * 16);
+    for (int s = 0; s < VM_KS; ++s) boff[s] = l16 * VM_COL_BYTES + (((4 * s + kc) ^ (l16 & (geo::CPR - 1))) * 16);
 
     f32x4 acc[2][RB];
 #pragma unroll
@@ -145,7 +154,7 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
                 for (int rb = 0; rb < RB; ++rb) {
                     // the next tile's loads go out early in this tile (its buffer is idle since the last barrier),
                     // so that they have landed long before the barrier at the end
-                    if (cb < VM_CB / 2 && (s == 1 || s == 3) && rb == 0) issue_load(tn, 2 * cb + (s >> 1), nxt);
+                    if (cb < VM_CB / 2 && (s & 1) && rb == 0) issue_load(tn, geo::LPC * cb + (s >> 1), nxt);
                     // RB independent accumulator chains, taken in turns (a chain's next link is RB MFMAs later)
                     if (s == 0)
                         acc[pp][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[s], a[rb][s], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
@@ -154,8 +163,9 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
                     // after its last use in this block, refill the fragment slot for the next block
                     if (rb == RB - 1 && cb + 1 < VM_CB)
                         b[s] = *reinterpret_cast<const bf16x8 *>(cur + (cb + 1) * 16 * VM_COL_BYTES + boff[s]);
-                    // drain the previous column block's accumulators (complete since >= RB MFMAs): one value per MFMA
-                    sum[rb][s] += fabsf(acc[pp ^ 1][rb][s]);
+                    // drain the previous column block's accumulators (complete since >= RB MFMAs): 4 / KS values per MFMA
+#pragma unroll
+                    for (int v = 0; v < 4 / VM_KS; ++v) sum[rb][s * (4 / VM_KS) + v] += fabsf(acc[pp ^ 1][rb][s * (4 / VM_KS) + v]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -189,20 +199,21 @@ __global__ __launch_bounds__(VM_THREADS, 2) void vproj_mfma_kernel(const bf16_t 
 
 bool vproj_mfma_supported(const Dims &d)
 {
-    return d.dh == VM_DH && d.dm % VM_TN == 0 && (size_t)d.dm * d.H * d.dh * 2 < ((size_t)1 << 31) &&
+    return (d.dh == 128 || d.dh == 64) && d.dm % (VM_TILE_BYTES / (d.dh * 2)) == 0 &&
+           (size_t)d.dm * d.H * d.dh * 2 < ((size_t)1 << 31) &&
            ((long long)d.batch * d.H + 8) * (d.n / 64 + 2) < (1ll << 31);
 }
 
-template <int RB>
+template <int DH, int RB>
 static void launch_rb(const Dims &d, const void *v, const void *w_t, float *vnorm, hipStream_t s)
 {
     const int rows_per_wg = VM_WAVES * RB * 16;
     const int row_tiles = (d.n + rows_per_wg - 1) / rows_per_wg;
     const int heads = d.batch * d.H;
-    const int pair = (size_t)2 * VM_DH * d.dm * 2 <= ((size_t)2 << 20) ? 1 : 0; // two slices within 2 MiB
+    const int pair = (size_t)2 * DH * d.dm * 2 <= ((size_t)2 << 20) ? 1 : 0; // two slices within 2 MiB
     const int hpx = (heads + 7) / 8;
     const long long wgs = 8ll * (pair ? 2 * ((hpx + 1) / 2) : hpx) * row_tiles; // 8 XCDs x heads (in pairs) x row tiles
-    hipLaunchKernelGGL((vproj_mfma_kernel<RB>), dim3((unsigned)wgs), dim3(VM_THREADS), 0, s, (const bf16_t *)v,
+    hipLaunchKernelGGL((vproj_mfma_kernel<DH, RB>), dim3((unsigned)wgs), dim3(VM_THREADS), 0, s, (const bf16_t *)v,
                        (const bf16_t *)w_t, vnorm, d.H, d.G, d.n, d.dm, d.vs[0], d.vs[1], d.vs[2], row_tiles, heads, pair);
 }
 
@@ -211,8 +222,9 @@ hipError_t launch_vproj_mfma(const Dims &d, const void *v, const void *w_t, floa
     // 7 row blocks per wave stream W_O 14 % less often than 6, but the workgroups are longer; measured, that wins
     // once the launch has many rounds of workgroups (1.4 % at 128K) and loses on short launches (2 % at 32K)
     const long long wgs7 = (long long)d.batch * d.H * ((d.n + VM_WAVES * 7 * 16 - 1) / (VM_WAVES * 7 * 16));
-    if (wgs7 >= 4096) launch_rb<7>(d, v, w_t, vnorm, s);
-    else launch_rb<6>(d, v, w_t, vnorm, s);
+    if (d.dh == 64) launch_rb<64, 6>(d, v, w_t, vnorm, s);
+    else if (wgs7 >= 4096) launch_rb<128, 7>(d, v, w_t, vnorm, s);
+    else launch_rb<128, 6>(d, v, w_t, vnorm, s);
     return hipGetLastError();
 }
 

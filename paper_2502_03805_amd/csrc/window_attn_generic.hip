@@ -7,12 +7,13 @@
 //   reduce  per window row: merge the chunk partials to (max, 1 / sum [/ W])
 //   pass 2  per key: a_i = sum_w exp(s_wi - max_w) * inv_w
 // One thread owns one key (its row stays in registers); the window queries of the head sit
-// in LDS and are read as broadcasts.
+// in LDS, GEN_WB rows at a time, and are read as broadcasts.
 #include "common.hpp"
 
 namespace ckv {
 
 constexpr int GEN_THREADS = 256; // keys per workgroup of the generic attention kernels
+constexpr int GEN_WB = 64;       // window rows staged in LDS at a time (longer windows take several rounds)
 
 template <typename T> struct Vec16;
 template <> struct Vec16<float> { static constexpr int N = 4; };
@@ -77,40 +78,45 @@ __global__ __launch_bounds__(GEN_THREADS) void attn_stats_generic_kernel(
     int chunks, float scale, int64_t ks0, int64_t ks1, int64_t ks2, int causal)
 {
     extern __shared__ float smem[];
-    float *q_lds = smem;               // [W][DH]
-    float *red = smem + (size_t)W * DH; // [W][4] wave partials
+    float *q_lds = smem;                      // [GEN_WB][DH]
+    float *red = smem + (size_t)GEN_WB * DH;  // [GEN_WB][4] wave maxima, then [GEN_WB][4] wave sums
     const int chunk = blockIdx.x, h = blockIdx.y, bi = blockIdx.z;
     const int g = h / G;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    stage_queries<T, DH>(q + ((size_t)bi * H + h) * (size_t)W * DH, W, q_lds);
     const int i = chunk * GEN_THREADS + threadIdx.x;
     const bool valid = i < n;
     // with the causal tail, key i is seen by window rows w >= i - (n - W) only
     const int first_w = causal ? max(0, i - (n - W)) : 0;
     float kr[DH];
     load_row<T, DH>(k + bi * ks0 + g * ks1 + (int64_t)(valid ? i : n - 1) * ks2, kr);
-    __syncthreads();
-    for (int w = 0; w < W; ++w) {
-        const float s = (valid && w >= first_w) ? scale * dot_lds<DH>(q_lds + w * DH, kr) : -INFINITY;
-        const float m = wave_max(s);
-        if (lane == 0) red[w * 4 + wave] = m;
-    }
-    __syncthreads();
-    for (int w = 0; w < W; ++w) {
-        // a chunk may hold no visible key for this row (max = -inf): its partial sum is 0
-        const float m = fmaxf(fmaxf(fmaxf(red[w * 4], red[w * 4 + 1]), fmaxf(red[w * 4 + 2], red[w * 4 + 3])), -1.0e30f);
-        const bool seen = valid && w >= first_w;
-        const float s = seen ? scale * dot_lds<DH>(q_lds + w * DH, kr) : -INFINITY;
-        const float e = wave_sum(seen ? __expf(s - m) : 0.f);
-        if (lane == 0) red[W * 4 + w * 4 + wave] = e;
-    }
-    __syncthreads();
-    for (int w = threadIdx.x; w < W; w += GEN_THREADS) {
-        const float m = fmaxf(fmaxf(fmaxf(red[w * 4], red[w * 4 + 1]), fmaxf(red[w * 4 + 2], red[w * 4 + 3])), -1.0e30f);
-        const float l = red[W * 4 + w * 4] + red[W * 4 + w * 4 + 1] + red[W * 4 + w * 4 + 2] + red[W * 4 + w * 4 + 3];
-        float *dst = part + ((((size_t)bi * H + h) * W + w) * (size_t)chunks + chunk) * 2;
-        dst[0] = m;
-        dst[1] = l;
+    for (int w0 = 0; w0 < W; w0 += GEN_WB) { // the window in rounds of GEN_WB rows
+        const int wb = min(GEN_WB, W - w0);
+        stage_queries<T, DH>(q + (((size_t)bi * H + h) * (size_t)W + w0) * DH, wb, q_lds);
+        __syncthreads();
+        for (int w = 0; w < wb; ++w) {
+            const float s = (valid && w0 + w >= first_w) ? scale * dot_lds<DH>(q_lds + w * DH, kr) : -INFINITY;
+            const float m = wave_max(s);
+            if (lane == 0) red[w * 4 + wave] = m;
+        }
+        __syncthreads();
+        for (int w = 0; w < wb; ++w) {
+            // a chunk may hold no visible key for this row (max = -inf): its partial sum is 0
+            const float m = fmaxf(fmaxf(fmaxf(red[w * 4], red[w * 4 + 1]), fmaxf(red[w * 4 + 2], red[w * 4 + 3])), -1.0e30f);
+            const bool seen = valid && w0 + w >= first_w;
+            const float s = seen ? scale * dot_lds<DH>(q_lds + w * DH, kr) : -INFINITY;
+            const float e = wave_sum(seen ? __expf(s - m) : 0.f);
+            if (lane == 0) red[GEN_WB * 4 + w * 4 + wave] = e;
+        }
+        __syncthreads();
+        for (int w = threadIdx.x; w < wb; w += GEN_THREADS) {
+            const float m = fmaxf(fmaxf(fmaxf(red[w * 4], red[w * 4 + 1]), fmaxf(red[w * 4 + 2], red[w * 4 + 3])), -1.0e30f);
+            const float l = red[GEN_WB * 4 + w * 4] + red[GEN_WB * 4 + w * 4 + 1] + red[GEN_WB * 4 + w * 4 + 2] +
+                            red[GEN_WB * 4 + w * 4 + 3];
+            float *dst = part + ((((size_t)bi * H + h) * W + w0 + w) * (size_t)chunks + chunk) * 2;
+            dst[0] = m;
+            dst[1] = l;
+        }
+        __syncthreads(); // the next round overwrites the staged queries and the partials
     }
 }
 
@@ -139,21 +145,26 @@ __global__ __launch_bounds__(GEN_THREADS) void attn_colsum_generic_kernel(
     int H, int G, int n, int W, float scale, int64_t ks0, int64_t ks1, int64_t ks2, int causal)
 {
     extern __shared__ float smem[];
-    float *q_lds = smem;                 // [W][DH]
-    float *st = smem + (size_t)W * DH;   // [W][2]
+    float *q_lds = smem;                       // [GEN_WB][DH]
+    float *st = smem + (size_t)GEN_WB * DH;    // [GEN_WB][2]
     const int chunk = blockIdx.x, h = blockIdx.y, bi = blockIdx.z;
     const int g = h / G;
-    stage_queries<T, DH>(q + ((size_t)bi * H + h) * (size_t)W * DH, W, q_lds);
-    for (int e = threadIdx.x; e < 2 * W; e += blockDim.x) st[e] = stats[((size_t)bi * H + h) * (size_t)W * 2 + e];
     const int i = chunk * GEN_THREADS + threadIdx.x;
     const bool valid = i < n;
     float kr[DH];
     load_row<T, DH>(k + bi * ks0 + g * ks1 + (int64_t)(valid ? i : n - 1) * ks2, kr);
-    __syncthreads();
+    const int first_w = causal ? max(0, i - (n - W)) : 0;
     float acc = 0.f;
-    for (int w = causal ? max(0, i - (n - W)) : 0; w < W; ++w) {
-        const float s = scale * dot_lds<DH>(q_lds + w * DH, kr);
-        acc += __expf(s - st[2 * w]) * st[2 * w + 1];
+    for (int w0 = 0; w0 < W; w0 += GEN_WB) { // the window in rounds of GEN_WB rows, rows added in ascending order
+        const int wb = min(GEN_WB, W - w0);
+        stage_queries<T, DH>(q + (((size_t)bi * H + h) * (size_t)W + w0) * DH, wb, q_lds);
+        for (int e = threadIdx.x; e < 2 * wb; e += blockDim.x) st[e] = stats[(((size_t)bi * H + h) * (size_t)W + w0) * 2 + e];
+        __syncthreads();
+        for (int w = max(0, first_w - w0); w < wb; ++w) {
+            const float s = scale * dot_lds<DH>(q_lds + w * DH, kr);
+            acc += __expf(s - st[2 * w]) * st[2 * w + 1];
+        }
+        __syncthreads(); // the next round overwrites the staged queries
     }
     if (valid) a_raw[((size_t)bi * H + h) * (size_t)n + i] = acc;
 }
@@ -161,7 +172,7 @@ __global__ __launch_bounds__(GEN_THREADS) void attn_colsum_generic_kernel(
 template <typename T, int DH>
 static hipError_t stats_generic_t(const Dims &d, const void *q, const void *k, float *part, int chunks, hipStream_t s)
 {
-    const size_t lds = ((size_t)d.W * DH + (size_t)d.W * 8) * sizeof(float);
+    const size_t lds = ((size_t)GEN_WB * DH + (size_t)GEN_WB * 8) * sizeof(float);
     dim3 grid(chunks, d.H, d.batch);
     hipLaunchKernelGGL((attn_stats_generic_kernel<T, DH>), grid, dim3(GEN_THREADS), lds, s, (const T *)q, (const T *)k,
                        part, d.H, d.G, d.n, d.W, chunks, d.scale, d.ks[0], d.ks[1], d.ks[2], d.causal);
@@ -172,7 +183,7 @@ template <typename T, int DH>
 static hipError_t colsum_generic_t(const Dims &d, const void *q, const void *k, const float *stats, float *a_raw,
                                    hipStream_t s)
 {
-    const size_t lds = ((size_t)d.W * DH + (size_t)d.W * 2) * sizeof(float);
+    const size_t lds = ((size_t)GEN_WB * DH + (size_t)GEN_WB * 2) * sizeof(float);
     dim3 grid((d.n + GEN_THREADS - 1) / GEN_THREADS, d.H, d.batch);
     hipLaunchKernelGGL((attn_colsum_generic_kernel<T, DH>), grid, dim3(GEN_THREADS), lds, s, (const T *)q,
                        (const T *)k, stats, a_raw, d.H, d.G, d.n, d.W, d.scale, d.ks[0], d.ks[1], d.ks[2], d.causal);

@@ -578,13 +578,20 @@ ODD_SHAPES = {
     "f32_dh64_g3_w1_dm32": dict(base="tiny", n_q_heads=6, n_kv_heads=2, n_ctx=257, window=1, d_model=32, pool_kernel=3,
                                 budget=40),
     "bf16_dh64_g2": dict(base="llama32k", n_q_heads=4, n_kv_heads=2, head_dim=64, n_ctx=515, window=16, d_model=96, budget=100),
+    # windows past what the matrix-core sweeps hold in registers (vector-ALU sweeps, the window staged in rounds)
+    "w200_bf16": dict(base="llama32k", n_q_heads=4, n_kv_heads=2, n_ctx=600, window=200, d_model=128, budget=100),
+    "w_equals_n_300_f32": dict(base="tiny", n_q_heads=2, n_kv_heads=1, n_ctx=300, window=300, d_model=64, budget=50),
+    # wave-private matrix-core sweeps: 128-row window (four row blocks per head), 100-row window, d_h = 64 with a 5:1 group
+    "w128_g2_wave": dict(base="llama32k", n_q_heads=4, n_kv_heads=2, n_ctx=900, window=128, d_model=128, budget=200),
+    "w100_mha_wave": dict(base="llama32k", n_q_heads=2, n_kv_heads=2, n_ctx=333, window=100, d_model=128, budget=60),
+    "dh64_g5_w64_wave": dict(base="llama32k", n_q_heads=10, n_kv_heads=2, head_dim=64, n_ctx=1100, window=64, d_model=128, budget=300),
 }
 
 
 @pytest.mark.parametrize("shape", sorted(ODD_SHAPES))
 def test_odd_shapes_every_entry_point(P, shape):
-    """Group sizes 1, 2, 3, 7, 12 and 16, windows 1 to 96, the smallest d_model, both dtypes and head sizes: whole pass,
-    allocation and diagnostics against the oracle."""
+    """Group sizes 1, 2, 3, 5, 7, 12 and 16, windows 1 to 300 (= n), the smallest d_model, both dtypes and head sizes,
+    every attention code path: whole pass, allocation and diagnostics against the oracle."""
     kw = dict(ODD_SHAPES[shape])
     cfg = CONFIGS[kw.pop("base")].with_(**kw)
     t = make_layer(cfg)
