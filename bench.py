@@ -191,7 +191,8 @@ class Workload:
             torch.cuda.synchronize()
         self.budget = torch.full((b, Hkv), B, dtype=torch.int32, device="cuda")
         self.lanes = []
-        for _ in range(max(1, n_streams)):
+        self.use_lanes = max(1, n_streams)   # lanes the steps rotate over (one more is kept for the two-stream extra)
+        for _ in range(max(2, n_streams)):
             self.lanes.append(dict(
                 stream=torch.cuda.Stream(),
                 ws=torch.empty(P.workspace_bytes(self.desc, B), dtype=torch.uint8, device="cuda"),
@@ -216,14 +217,14 @@ class Workload:
         import torch
         P, cfg = self.P, self.cfg
         dev = self.sets[s % len(self.sets)]
-        lane = self.lanes[s % len(self.lanes)] if lane is None else lane
+        lane = self.lanes[s % self.use_lanes] if lane is None else lane
         st = lane["stream"]
-        if len(self.lanes) > 1 and self.score_done is not None:
+        if self.use_lanes > 1 and self.score_done is not None:
             st.wait_event(self.score_done)
         P.criticalkv_score_profiled(self.desc, dev["q_win"], dev["k"], dev["v"], dev["w_o"], lane["attn"], lane["crit"],
                                     lane["vnorm"] if with_vnorm else None, workspace=lane["ws"],
                                     stage_events=self.none_events if stage_events is None else stage_events, stream=st)
-        if len(self.lanes) > 1:
+        if self.use_lanes > 1:
             self.score_done = torch.cuda.Event()
             self.score_done.record(st)
         P.criticalkv_select(self.desc, lane["attn"], lane["crit"], self.budget, cfg.alpha, self.B, lane["idx"], lane["count"],
@@ -263,7 +264,7 @@ class Workload:
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         ms = [self.ev.ms(ctypes.c_void_p(a[self.vslot]), ctypes.c_void_p(a[self.vend])) for a in step_events]
-        for lane in self.lanes[:min(len(self.lanes), steps)]:
+        for lane in self.lanes[:min(self.use_lanes, steps)]:
             assert int(lane["count"].min()) == self.B and int(lane["count"].max()) == self.B
         return (t1 - t0) * 1e3 / steps, max(float(self.np.mean(ms)), 1e-6)
 
@@ -427,7 +428,7 @@ def main():
     with_oracle = not args.no_cpu_baseline
     wl = Workload(P, cfg, args.norm, args.streams, nsets, args.gen_threads, ev, want_vnorm=with_oracle and args.norm != "none")
     sets, lanes, desc, B = wl.sets, wl.lanes, wl.desc, wl.B
-    n_streams = len(lanes)
+    n_streams = wl.use_lanes
     l2 = args.norm == "l2"
 
     if args.copy_probe:
@@ -446,6 +447,15 @@ def main():
     # the sustained rate: the same steps back to back for at least --sustained-ms on one stream, with the board's
     # power and clock sampled meanwhile
     sustained_ms, sustained_steps, power_under_load = wl.sustained(args.sustained_ms, ms_per_step, sample_power=True)
+    # throughput mode: independent layers issued on two streams, so that one layer's selection and gather (latency
+    # bound, nearly idle kernels) run under the next layer's projection
+    two_stream_ms = None
+    if n_streams == 1:
+        wl.use_lanes = 2
+        wl.sustained(50.0, ms_per_step)
+        two_stream_ms, _, _ = wl.sustained(args.sustained_ms / 2, ms_per_step)
+        wl.use_lanes, wl.score_done = 1, None
+        torch.cuda.synchronize()
     # a multi-layer workload: whole sweeps over all its layers in order, each timed on its own
     sweep_ms = None
     if cfg.n_layers > 1 and nsets == cfg.n_layers:
@@ -673,6 +683,7 @@ def main():
               "sustained_ms_per_step": round(sustained_ms, 4), "sustained_steps": sustained_steps,
               "sustained_m_entries_per_s": round(entries / (sustained_ms * 1e-3) / 1e6, 2),
               "sustained_vs_timed_pct": round(diff_pct, 2),
+              "two_stream_sustained_ms_per_step": None if two_stream_ms is None else round(two_stream_ms, 4),
               "graph_replay_ms_per_step": graph_ms,
               "tokens_per_s": round(b * n / (ms_per_step * 1e-3), 1),
               "gpu_power_state": gpu_power_state(), "board_power_under_load": power_under_load}

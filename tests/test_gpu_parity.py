@@ -805,6 +805,24 @@ def test_pass_replays_from_a_hip_graph(P):
     compare_selection(replayed["idx"].cpu().numpy(), replayed["count"].cpu().numpy(), ref, B, cfg.alpha)
 
 
+def test_default_path_is_bitwise_repeatable(P):
+    """Three runs of the whole pass on the same inputs (fresh workspaces and outputs each time, other work in
+    between) give identical scores, index sets and compacted rows: every cross-workgroup decision is made on
+    integer counts, every floating-point sum has a fixed order."""
+    for cfg, wo in ((reduced(CONFIGS["llama32k"], 20011, d_model=1024), True),
+                    (reduced(CONFIGS["qwen128k"], 6007, d_model=512), True), (CONFIGS["tiny"], False)):
+        t = make_layer(cfg)
+        runs = []
+        for r in range(3):
+            runs.append(run_gpu_pass(P, cfg, t, cfg.budget, cfg.alpha, wo_out_in=wo))
+            if r == 0:  # unrelated work on the device between the runs
+                other = reduced(CONFIGS["llama32k"], 1037, d_model=256)
+                run_gpu_pass(P, other, make_layer(other), other.budget, other.alpha, wo_out_in=True)
+        for r in runs[1:]:
+            for name in ("attn", "crit", "vnorm", "idx", "count", "k_out", "v_out"):
+                assert np.array_equal(getattr(runs[0], name), getattr(r, name)), (cfg.name, name)
+
+
 def test_prepared_projection_layout_matches_the_per_call_one(P):
     """criticalkv_prepare_wo once, then criticalkv_score with CKV_WO_OUT_IN on the prepared copy: bit for bit the
     scores that criticalkv_score gives when it is handed the canonical projection and re-lays it out itself."""
