@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per launch of the projection kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00 after calibration against a 1 GiB device copy); the runs and the
 # calibration are written up in profiles/whole_pass_llama_hbm_counters.md.  None where not measured.
-VPROJ_TRAFFIC_BYTES = {"llama32k": int(190.0 * 2**20), "llama128k": int(607.3 * 2**20)}
+VPROJ_TRAFFIC_BYTES = {"llama32k": int(190.0 * 2**20), "llama128k": int(607.1 * 2**20), "qwen128k": int(1751.4 * 2**20)}
 # the same for the Gram-matrix kernel of the L2 variant (95.2 + 4.0 and 383.3 + 16.0 MiB)
 L2_TRAFFIC_BYTES = {"llama32k": int(99.2 * 2**20), "llama128k": int(399.3 * 2**20)}
 
@@ -383,6 +383,10 @@ def main():
                     "mistral_prefill: all 32 layers resident, each with its own projection)")
     ap.add_argument("--sustained-ms", type=float, default=500.0, help="length of the back-to-back loop behind sustained_ms_per_step")
     ap.add_argument("--no-other-workloads", action="store_true", help="skip the other workload shapes (other_workloads)")
+    ap.add_argument("--lean", action="store_true",
+                    help="for profiler runs: only the timed steps, the sustained loop and the stage breakdown (no other "
+                         "workloads, no oracle, no two-stream loop, no graph replay), so that a kernel trace holds the "
+                         "one-stream pass alone")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle (cpu_baseline and parity)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0,
                     help="tokens per kv head the oracle runs on (0 = the whole layer, at most 131072)")
@@ -418,6 +422,8 @@ def main():
     from workload import CONFIGS
 
     P.load()
+    if args.lean:
+        args.no_other_workloads = args.no_cpu_baseline = True
     cfg = CONFIGS[args.workload]
     b, H, Hkv, n, dh, dm = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_ctx, cfg.head_dim, cfg.d_model
     kv_bytes = 2 * b * Hkv * n * dh * (2 if cfg.dtype == "bf16" else 4)
@@ -450,7 +456,7 @@ def main():
     # throughput mode: independent layers issued on two streams, so that one layer's selection and gather (latency
     # bound, nearly idle kernels) run under the next layer's projection
     two_stream_ms = None
-    if n_streams == 1:
+    if n_streams == 1 and not args.lean:
         wl.use_lanes = 2
         wl.sustained(50.0, ms_per_step)
         two_stream_ms, _, _ = wl.sustained(args.sustained_ms / 2, ms_per_step)
@@ -538,6 +544,8 @@ def main():
     # carry no timing on replay, so the headline stays on the eager steps whose projection kernel is event-marked.
     graph_ms = None
     try:
+        if args.lean:
+            raise RuntimeError("skipped (--lean)")
         graphs = []
         with torch.cuda.stream(stream):
             for dev in sets[:4]:

@@ -371,13 +371,13 @@ bool attn_wave_supported(const Dims &d)
 }
 
 // Keys per wave (it sets the number of waves per head).  Many keys spread a wave's fixed cost (its query fragments:
-// up to 32 KiB) over more key blocks; few give the chip enough waves (it holds 8 per CU, 2048 in all).  The largest
-// power of two that still yields one full round of waves, at least AM_MIN_KPW keys (measured: 512-1024 keys at a
-// 128K context, 128-256 at 32K).
+// up to 32 KiB) over more key blocks; few give the chip enough waves (it holds 8 per CU, 2048 in all).  Measured
+// on the 5:1 group with a 64-row window at a 128K context: 1024 keys per wave is the best (512 and 2048 are 4-7 %
+// slower, 256 is 14 % slower), so: 1024, halved while that leaves less than one full round of waves.
 static int attn_kpw(const Dims &d, int groups)
 {
     const long long per_range = (long long)d.batch * d.Hkv * groups;
-    int kpw = 2048;
+    int kpw = 1024;
     while (kpw > AM_MIN_KPW && per_range * ((d.n + kpw - 1) / kpw) < 2048) kpw >>= 1;
     return kpw;
 }
@@ -390,13 +390,14 @@ static AttnArgs make_args(const Dims &d, const void *q, const void *k)
     A.qbs = (d.W + 31) / 32;
     // Heads per wave: every wave runs all of its hpw * qbs row blocks (a last group with fewer heads works on zero
     // queries for the rest), so hpw is the choice with the least wave work in all, a key block's own cost (its
-    // loads and fragment reads) counted as a quarter of a row block's; ties go to the larger hpw.
+    // loads and fragment reads) counted like one row block's; ties go to the larger hpw (measured on the 5:1 group
+    // with a 64-row window: two heads per wave 1.5 % faster than one).
     A.hpw = 1;
     {
         const int most = AM_MAX_QB / A.qbs < d.G ? AM_MAX_QB / A.qbs : d.G;
         int best = 1 << 30;
         for (int h = 1; h <= (most > 0 ? most : 1); ++h) {
-            const int cost = ((d.G + h - 1) / h) * (1 + 4 * h * A.qbs);
+            const int cost = ((d.G + h - 1) / h) * (1 + h * A.qbs);
             if (cost <= best) { best = cost; A.hpw = h; }
         }
     }
