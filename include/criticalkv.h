@@ -156,7 +156,9 @@ CKV_API int criticalkv_prepare_gram(const ckv_layer_desc *desc, const void *w_o,
  * criticalkv_score with per-stage timing marks, for benchmarks and profiles (the scores are the same).
  * stage_events is a HOST array of 2 * CKV_N_SCORE_STAGES hipEvent_t (as void*) created by the caller with
  * timing enabled; entry 2*s is recorded on the stream before stage s, entry 2*s+1 after it.  NULL entries
- * (or a NULL array) are skipped.  The caller reads the events after synchronising.
+ * (or a NULL array) are skipped.  The caller reads the events after synchronising.  The stages are issued in the
+ * order layout, projection, first sweep, second sweep, combine (the projection hardly touches HBM, so a previous
+ * kernel's pending write-backs drain under it and not under the bandwidth-bound sweeps).
  */
 #define CKV_STAGE_WO_LAYOUT 0   /* layout change of a canonical w_o (empty with CKV_WO_OUT_IN) */
 #define CKV_STAGE_ATTN_STATS 1  /* first key sweep: row max and sum of exp                      */

@@ -948,8 +948,11 @@ def test_profiled_score_records_every_stage_and_changes_nothing(P):
     ms = {name: events[2 * i].elapsed_time(events[2 * i + 1]) for i, name in enumerate(P.STAGES)}
     assert all(v >= 0.0 for v in ms.values()), ms
     assert ms["vproj"] == max(ms.values()) and ms["wo_layout"] > 0.0, ms
-    for i in range(len(P.STAGES) - 1):            # stages follow each other on the stream
-        assert events[2 * i + 1].elapsed_time(events[2 * i + 2]) >= 0.0
+    # the stages follow each other on the stream in the order the library issues them: the projection before
+    # the two key sweeps
+    order = [P.STAGES.index(name) for name in ("wo_layout", "vproj", "attn_stats", "attn_colsum", "combine")]
+    for a, b in zip(order, order[1:]):
+        assert events[2 * a + 1].elapsed_time(events[2 * b]) >= 0.0, (P.STAGES[a], P.STAGES[b])
     # a NULL entry is skipped: only the projection marked
     arr2 = (ctypes.c_void_p * len(events))()
     v = P.STAGES.index("vproj")
