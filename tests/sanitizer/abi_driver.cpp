@@ -92,6 +92,11 @@ int main()
     CHECK(criticalkv_compact(&d, p, p, i, nullptr, 10, p, p, nullptr) == CKV_E_INVALID_ARG);
     CHECK(criticalkv_compact(&d, p, p, i, i, 0, p, p, nullptr) == CKV_E_INVALID_ARG);
     CHECK(criticalkv_prepare_wo(&d, p, p, nullptr) == CKV_E_INVALID_ARG);
+    CHECK(criticalkv_probe_mfma_bf16(nullptr, 10, nullptr, (float *)p, nullptr) == CKV_E_INVALID_ARG);
+    CHECK(criticalkv_probe_mfma_bf16(buf + 8, 10, nullptr, (float *)p, nullptr) == CKV_E_INVALID_ARG);
+    CHECK(criticalkv_probe_mfma_bf16(p, 0, nullptr, (float *)p, nullptr) == CKV_E_INVALID_ARG);
+    CHECK(criticalkv_probe_hbm_read(p, 8, (uint32_t *)p, nullptr) == CKV_E_INVALID_ARG);
+    CHECK(criticalkv_probe_hbm_read(nullptr, 4096, (uint32_t *)p, nullptr) == CKV_E_INVALID_ARG);
     ckv_layer_desc g = good();
     g.d_model = 512; g.norm = CKV_NORM_L2;
     CHECK(criticalkv_gram_bytes(&g) == (size_t)8 * 2 * 128 * 128 * 2);
