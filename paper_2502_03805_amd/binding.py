@@ -8,7 +8,6 @@ from __future__ import annotations
 
 import ctypes
 import os
-from dataclasses import dataclass
 from typing import Optional
 
 PKG = os.path.dirname(os.path.abspath(__file__))
