@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # calibration are written up in profiles/whole_pass_llama_hbm_counters.md.  None where not measured.
 VPROJ_TRAFFIC_BYTES = {"llama32k": int(190.0 * 2**20), "llama128k": int(607.1 * 2**20), "qwen128k": int(1751.4 * 2**20)}
 # the same for the Gram-matrix kernel of the L2 variant (95.2 + 4.0 and 383.3 + 16.0 MiB)
-L2_TRAFFIC_BYTES = {"llama32k": int(99.2 * 2**20), "llama128k": int(399.3 * 2**20)}
+L2_TRAFFIC_BYTES = {"llama32k": int(73.8 * 2**20), "llama128k": int(294.4 * 2**20)}
 
 
 class HipEvents:
@@ -679,7 +679,7 @@ def main():
                     "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
                     "traffic": None, "avg_launch_ms": round(vproj_avg, 4), "algorithmic_bytes_per_launch": sweep_bytes}
     else:
-        roofline = {"kernel": "vproj_mfma_kernel" if args.norm == "l1" else "vproj_l2_mfma_kernel", "bound": "mfma",
+        roofline = {"kernel": "vproj_mfma_kernel" if args.norm == "l1" else "vproj_l2_resident_kernel", "bound": "mfma",
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                     "traffic": (VPROJ_TRAFFIC_BYTES if args.norm == "l1" else L2_TRAFFIC_BYTES).get(cfg.name),

@@ -11,11 +11,12 @@
 //                 below the diagonal doubled, those above dropped -- the quadratic form is unchanged and
 //                 12 of the 32 block products fall away) and splits it into two bf16 matrices G_hi + G_lo
 //                 (error ~2^-17 relative), stored [head][u][t]
-//   l2 kernel     one workgroup per (group of row tiles, kv head): a tile's V rows stay in registers as MFMA
-//                 B fragments for all G query heads of the group (V is read once); per head the two G
-//                 matrices (64 KiB) stream through a double-buffered LDS and  Y^T = G V^T  is accumulated
-//                 with v_mfma_f32_16x16x32_bf16 over G_hi and G_lo; the epilogue multiplies by v again:
+//   l2 kernel     one workgroup per (query head, range of rows) with the head's two G matrices (64 KiB) resident in
+//                 LDS; V rows stream through registers as MFMA B fragments,  Y^T = G V^T  is accumulated with
+//                 v_mfma_f32_16x16x32_bf16 over G_hi and G_lo, and the epilogue multiplies by v again:
 //                 N^2_i = sum_u Y[i,u] v[i,u].
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace ckv {
@@ -26,9 +27,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int GL_DH = 128;
 constexpr int GL_SLICES = 4;          // d_model slices of the Gram partial sums
 constexpr int GL_TILE_C = 128;        // columns of W_O staged per LDS tile in gram_partial
-constexpr int GL_WAVES = 8;            // one workgroup of 8 waves per CU
-constexpr int GL_THREADS = GL_WAVES * 64;
-constexpr int GL_RB = 4;              // 16-row blocks per wave and row tile
 constexpr int GL_G_BYTES = GL_DH * GL_DH * 2; // one bf16 Gram matrix: 32 KiB
 
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -105,141 +103,165 @@ __global__ __launch_bounds__(256) void gram_finish_kernel(const float *__restric
     }
 }
 
-// N^h_i for the G query heads of one kv head and `passes` row tiles of 8 waves x GL_RB x 16 rows.
+// N^h_i for one query head and one range of rows, with the head's two Gram matrices resident in LDS.
 //
-// One workgroup of 8 waves per CU.  The work of a workgroup is a sequence of steps (row tile, query head);
-// a step needs that head's two Gram matrices (64 KiB) in LDS.  The matrices are double buffered (128 KiB):
-// the loads of step k + 1 are issued before the MFMAs of step k and are waited for after them, so one barrier
-// per step is the only synchronisation and the L2 latency of the matrices hides behind 160 MFMAs per wave.
-// A row tile's V fragments stay in registers for its G steps.
-__global__ __launch_bounds__(GL_THREADS) void vproj_l2_mfma_kernel(const bf16_t *__restrict__ v,
-                                                                    const bf16_t *__restrict__ gram,
-                                                                    float *__restrict__ vnorm, int H, int G, int n,
-                                                                    int64_t vs0, int64_t vs1, int64_t vs2, int passes)
+// One 4-wave workgroup per (query head, range of rows), two workgroups per CU.  The head's G_hi | G_lo (64 KiB)
+// are fetched once, at the start; after the one barrier that follows, every wave is on its own: it walks its
+// blocks of GR_RB x 16 rows, requests the next block's V fragments (global -> registers) before it starts on
+// the current one, and reads the Gram fragments it needs from LDS.  No barrier and no Gram traffic in the loop.
+// V is read once per query head; the workgroups of a kv group's heads that work on the same rows are neighbours
+// in launch order on one XCD (workgroup L of a 1-D grid runs on XCD L % 8), so the second to the last reader of
+// a row find it in that XCD's L2.
+constexpr int GR_WAVES = 4;
+constexpr int GR_RB = 4;
+constexpr int GR_BLOCK_ROWS = GR_RB * 16;
+
+__global__ __launch_bounds__(GR_WAVES * 64, 2) void vproj_l2_resident_kernel(const bf16_t *__restrict__ v,
+                                                                             const bf16_t *__restrict__ gram,
+                                                                             float *__restrict__ vnorm, int H, int G, int n,
+                                                                             int64_t vs0, int64_t vs1, int64_t vs2, int pairs,
+                                                                             int ranges, int rows_per_range)
 {
-    __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * GL_G_BYTES]; // 2 buffers x (G_hi | G_lo), XOR-swizzled
+    __shared__ __attribute__((aligned(1024))) char lds[2 * GL_G_BYTES]; // G_hi | G_lo, XOR-swizzled
     const int Hkv = H / G;
-    const int g = blockIdx.y % Hkv, bi = blockIdx.y / Hkv;
+    const int L = blockIdx.x, xcd = L & 7;
+    int r = L >> 3;
+    const int hl = r % G;
+    r /= G;
+    const int range = r % ranges;
+    const int pair = (r / ranges) * 8 + xcd;
+    if (pair >= pairs) return; // uniform over the workgroup
+    const int bi = pair / Hkv, g = pair % Hkv, h = g * G + hl;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, kc = lane >> 4;
-    const int rows_per_pass = GL_WAVES * GL_RB * 16;
-    const int tile_row0 = blockIdx.x * passes * rows_per_pass;
-    // row tiles that start inside the head (a uniform count: all waves take the same number of barriers)
-    const int my_passes = min(passes, (n - tile_row0 + rows_per_pass - 1) / rows_per_pass);
-    const int steps = my_passes * G;
+    const int row_begin = range * rows_per_range;            // a multiple of GR_BLOCK_ROWS
+    const int row_end = min(n, row_begin + rows_per_range);
+    if (row_begin >= row_end) return;                        // uniform over the workgroup
+    const int nblk = (row_end - row_begin + GR_BLOCK_ROWS - 1) / GR_BLOCK_ROWS;
     const bf16_t *vbase = v + bi * vs0 + g * vs1;
 
-    // 64 KiB of one head = 64 direct loads of 1 KiB, 8 per wave.  Row u of a matrix is 256 B = 16 chunks;
-    // chunk q is stored at slot q ^ f(u), f(u) = 4 * ((u / 8) % 4) + u % 4: the 16 rows that one MFMA A operand
-    // reads together (see below) have 16 different f, so their 16-byte reads fall on different banks.
-    auto issue_gram = [&](int step, int buf) {
-        const int h = g * G + step % G;
+    {   // the head's 64 KiB: 64 direct loads of 1 KiB, 16 per wave; row u of a matrix is 256 B = 16 chunks;
+        // chunk q sits at slot q ^ f(u), f(u) = 4 * ((u / 8) % 4) + u % 4: the 16 rows that one MFMA A operand reads
+        // together (see below) have 16 different f, so their 16-byte reads fall on different banks
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             (void *)(gram + (size_t)h * 2 * GL_DH * GL_DH), 0, 2 * GL_G_BYTES, 0x00020000);
 #pragma unroll
-        for (int j = 0; j < 64 / GL_WAVES; ++j) {
-            const int kib = j * GL_WAVES + wave;            // KiB index inside the 64 KiB: rows 4*kib .. 4*kib+3
+        for (int j = 0; j < 64 / GR_WAVES; ++j) {
+            const int kib = j * GR_WAVES + wave;
             const int urow = (kib * 4 + (lane >> 4)) & (GL_DH - 1);
             const int f = ((urow >> 3) & 3) * 4 + (urow & 3);
             const uint32_t voff = (uint32_t)(kib * 1024 + (lane >> 4) * 256 + (((lane & 15) ^ f) * 16));
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(lds + buf * 2 * GL_G_BYTES + kib * 1024), 16, voff, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(lds + kib * 1024), 16, voff, 0, 0, 0);
+        }
+    }
+    // V rows through a buffer descriptor over this kv head's rows (the host checks that they span less than 2 GiB, so
+    // 32-bit byte offsets do).  Rows past n - 1 re-read row n - 1 (never stored): the clamp is in the lane's
+    // offset, because the descriptor's range check does not see the scalar offset.
+    const __amdgpu_buffer_rsrc_t vrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)vbase, 0, (int)(((int64_t)(n - 1) * vs2 + GL_DH) * 2), 0x00020000);
+    const uint32_t row_bytes = (uint32_t)(vs2 * 2);
+    // a block's V fragments in two halves: k-chunks 0-1 (the row's first 128 bytes) and 2-3 (its second)
+    auto load_v_half = [&](int blk, int hf, bf16x8 (&dst)[GR_RB][2]) {
+        const int row0 = row_begin + blk * GR_BLOCK_ROWS;
+#pragma unroll
+        for (int rb = 0; rb < GR_RB; ++rb) {
+            const uint32_t voff = (uint32_t)min(row0 + rb * 16 + l16, n - 1) * row_bytes + (uint32_t)(kc * 16 + hf * 128);
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                dst[rb][s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(vrsrc, voff + s * 64, 0, 0));
         }
     };
-    // B fragments: this wave's rows of V (token i = lane % 16 of block rb, k = t)
-    auto load_v = [&](int pass, bf16x8 (&dst)[GL_RB][4]) {
-        const int row0 = tile_row0 + (pass * GL_WAVES + wave) * (GL_RB * 16);
-#pragma unroll
-        for (int rb = 0; rb < GL_RB; ++rb) {
-            const int row = min(row0 + rb * 16 + l16, n - 1);
-            const bf16_t *p = vbase + (int64_t)row * vs2 + kc * 8;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) dst[rb][s] = *reinterpret_cast<const bf16x8 *>(p + s * 32);
-        }
-    };
+    // Registers: the first halves of two blocks (the current one and the wave's next, requested a block ahead) and
+    // the second half of the current block only, requested when the block starts: the block-lower-triangular
+    // Gram matrix needs k-chunks 2-3 from its fifth 16-row slab on, 48 MFMAs into the block.
+    bf16x8 va[2][GR_RB][2], vb[GR_RB][2];
+    if (wave < nblk) load_v_half(wave, 0, va[0]);
+    __syncthreads(); // the Gram matrices have landed (every wave waits for its own loads first)
+    if (wave >= nblk) return; // after the only barrier
 
-    if (steps <= 0) return; // uniform over the workgroup
-    bf16x8 vf[GL_RB][4];
-    issue_gram(0, 0);
-    load_v(0, vf);
-    __syncthreads(); // waits for the direct loads of this wave, then for every wave
+    // The 16 rows u of G that one MFMA takes as its A operand are chosen so that the product's epilogue factor
+    // v[i][u] is already in the lane's registers: accumulator value j of lane (i, kc) belongs to A row
+    // m = 4 * kc + j, and that row is u(m) = 32 * sp + 8 * (m / 4) + 4 * half + m % 4 = 32 * sp + 8 * kc + 4 * half + j,
+    // i.e. element 4 * half + j of the lane's own V fragment of k-chunk sp.  (sp, half) = (ub / 2, ub % 2) covers all rows.
+    const int a_row = 8 * (l16 >> 2) + (l16 & 3);          // + 32 * sp + 4 * half
+    const int a_f = 4 * (l16 >> 2) + (l16 & 3);            // f(u) of that row: bits 3-4 and 0-1 of u
+    float *out = vnorm + ((size_t)bi * H + h) * (size_t)n;
 
-#pragma unroll 1
-    for (int step = 0; step < steps; ++step) {
-        const int pass = step / G, hl = step - pass * G, buf = step & 1;
-        if (step + 1 < steps) issue_gram(step + 1, buf ^ 1); // that buffer was last read in step - 1
-        const char *gl = lds + buf * 2 * GL_G_BYTES;
-        const int row0 = tile_row0 + (pass * GL_WAVES + wave) * (GL_RB * 16);
-
-        float nsq[GL_RB];
+    // One block of rows from register set CUR; the other set receives the wave's next block meanwhile.
+    auto block_step = [&](auto cur_c, int blk) {
+        constexpr int CUR = decltype(cur_c)::value;
+        load_v_half(blk, 1, vb);
+        load_v_half(blk + GR_WAVES, 0, va[CUR ^ 1]); // unconditional (clamped rows): the wait counts stay exact
+        float nsq[GR_RB];
 #pragma unroll
-        for (int rb = 0; rb < GL_RB; ++rb) nsq[rb] = 0.f;
-        // The 16 rows u of G that one MFMA takes as its A operand are chosen so that the product's epilogue factor
-        // v[i][u] is already in the lane's registers: accumulator value j of lane (i, kc) belongs to A row
-        // m = 4 * kc + j, and that row is u(m) = 32 * sp + 8 * (m / 4) + 4 * half + m % 4 = 32 * sp + 8 * kc + 4 * half + j,
-        // i.e. element 4 * half + j of the lane's own fragment vf[rb][sp].  (sp, half) = (ub / 2, ub % 2) covers all rows.
-        const int a_row = 8 * (l16 >> 2) + (l16 & 3);          // + 32 * sp + 4 * half
-        const int a_f = 4 * (l16 >> 2) + (l16 & 3);            // f(u) of that row: bits 3-4 and 0-1 of u
-        // fragments of 16 rows of G_hi (0-3) and G_lo (4-7); read one ub ahead of their use
-        bf16x8 gf[2][8];
-        // (rows of block sp meet the k-chunks s <= sp only: the stored matrices are block lower triangular)
-        auto read_g = [&](int ub, bf16x8 (&dst)[8]) {
-            const char *rowp = gl + (32 * (ub >> 1) + 4 * (ub & 1) + a_row) * 256;
+        for (int rb = 0; rb < GR_RB; ++rb) nsq[rb] = 0.f;
+        // fragments of 16 rows of G_hi (0-3) and G_lo (4-7) for one ub; the next ub's are requested into the same
+        // registers as soon as this ub's MFMAs are issued and arrive under its epilogue and the other wave's work
+        bf16x8 gf[8];
+        auto read_g = [&](int ub) {
+            const char *rowp = lds + (32 * (ub >> 1) + 4 * (ub & 1) + a_row) * 256;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                if (s > (ub >> 1)) continue; // static: the loop over ub is unrolled
+                if (s > (ub >> 1)) continue; // (rows of block sp meet the k-chunks s <= sp only)
                 const int slot = ((4 * s + kc) ^ a_f) * 16;
-                dst[s] = *reinterpret_cast<const bf16x8 *>(rowp + slot);
-                dst[4 + s] = *reinterpret_cast<const bf16x8 *>(rowp + GL_G_BYTES + slot);
+                gf[s] = *reinterpret_cast<const bf16x8 *>(rowp + slot);
+                gf[4 + s] = *reinterpret_cast<const bf16x8 *>(rowp + GL_G_BYTES + slot);
             }
         };
-        read_g(0, gf[0]);
+        read_g(0);
 #pragma unroll
         for (int ub = 0; ub < GL_DH / 16; ++ub) {
-            const int sp = ub >> 1, half = ub & 1, cur = ub & 1;
-            if (ub + 1 < GL_DH / 16) read_g(ub + 1, gf[cur ^ 1]);
-            // GL_RB independent accumulator chains taken in turns
-            f32x4 acc[GL_RB];
+            const int sp = ub >> 1, half = ub & 1;
+            f32x4 acc[GR_RB];
 #pragma unroll
-            for (int rb = 0; rb < GL_RB; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int rb = 0; rb < GR_RB; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s <= sp; ++s) {
 #pragma unroll
-                for (int rb = 0; rb < GL_RB; ++rb)
-                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gf[cur][4 + s], vf[rb][s], acc[rb], 0, 0, 0);
+                for (int rb = 0; rb < GR_RB; ++rb)
+                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gf[4 + s], s < 2 ? va[CUR][rb][s] : vb[rb][s - 2], acc[rb], 0, 0, 0);
 #pragma unroll
-                for (int rb = 0; rb < GL_RB; ++rb)
-                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gf[cur][s], vf[rb][s], acc[rb], 0, 0, 0);
+                for (int rb = 0; rb < GR_RB; ++rb)
+                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gf[s], s < 2 ? va[CUR][rb][s] : vb[rb][s - 2], acc[rb], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            if (ub + 1 < GL_DH / 16) read_g(ub + 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int rb = 0; rb < GL_RB; ++rb) {
+            for (int rb = 0; rb < GR_RB; ++rb) {
                 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-                const u32x4 w = __builtin_bit_cast(u32x4, vf[rb][sp]);
+                const u32x4 w = __builtin_bit_cast(u32x4, sp < 2 ? va[CUR][rb][sp] : vb[rb][sp - 2]);
                 const uint32_t w0 = w[2 * half], w1 = w[2 * half + 1];
                 nsq[rb] = fmaf(acc[rb][0], __uint_as_float(w0 << 16), nsq[rb]);
                 nsq[rb] = fmaf(acc[rb][1], __uint_as_float(w0 & 0xFFFF0000u), nsq[rb]);
                 nsq[rb] = fmaf(acc[rb][2], __uint_as_float(w1 << 16), nsq[rb]);
                 nsq[rb] = fmaf(acc[rb][3], __uint_as_float(w1 & 0xFFFF0000u), nsq[rb]);
             }
-            __builtin_amdgcn_sched_barrier(0); // keep the read-ahead distance at one ub (registers)
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // merge the four k-chunk lanes of a token, then one value per token
-        float *out = vnorm + ((size_t)bi * H + g * G + hl) * (size_t)n;
+        const int row0 = row_begin + blk * GR_BLOCK_ROWS;
 #pragma unroll
-        for (int rb = 0; rb < GL_RB; ++rb) {
+        for (int rb = 0; rb < GR_RB; ++rb) {
             float x = nsq[rb];
             x += __shfl_xor(x, 16);
             x += __shfl_xor(x, 32);
             const int row = row0 + rb * 16 + l16;
-            if (kc == 0 && row < n) out[row] = sqrtf(fmaxf(x, 0.f));
+            if (kc == 0 && row < row_end) out[row] = sqrtf(fmaxf(x, 0.f));
         }
-        // the next row tile's fragments replace this one's after its last step (they are waited for with the barrier)
-        if (hl == G - 1 && pass + 1 < my_passes) load_v(pass + 1, vf);
-        __syncthreads(); // the next step's matrices have landed (own loads waited first) and this buffer is free
+    };
+    for (int blk = wave; blk < nblk; blk += 2 * GR_WAVES) {
+        block_step(std::integral_constant<int, 0>{}, blk);
+        if (blk + GR_WAVES < nblk) block_step(std::integral_constant<int, 1>{}, blk + GR_WAVES);
     }
 }
 
-bool vproj_l2_mfma_supported(const Dims &d) { return d.dh == GL_DH && d.dm % (GL_SLICES * GL_TILE_C) == 0; }
+bool vproj_l2_mfma_supported(const Dims &d)
+{
+    // (the V rows of one kv head are addressed through a buffer descriptor with 32-bit byte offsets)
+    return d.dh == GL_DH && d.dm % (GL_SLICES * GL_TILE_C) == 0 &&
+           (((int64_t)(d.n - 1) * d.vs[2] + GL_DH) * 2) < ((int64_t)1 << 31);
+}
 
 size_t vproj_l2_gram_bytes(const Dims &d) { return (size_t)d.H * 2 * GL_DH * GL_DH * 2; }
 
@@ -259,16 +281,19 @@ hipError_t launch_gram(const Dims &d, const void *w_t, void *gram_out, void *par
 
 hipError_t launch_vproj_l2_mfma(const Dims &d, const void *v, const void *gram, float *vnorm, hipStream_t s)
 {
-    // row tiles per workgroup: aim at one workgroup per CU (256) for the whole launch, so that every CU streams
-    // the Gram matrices the same number of times and the launch has no partial last round
-    const int rows_per_pass = GL_WAVES * GL_RB * 16;
-    const long long total_rows = (long long)d.batch * d.Hkv * d.n;
-    int passes = (int)((total_rows + 128ll * rows_per_pass) / (256ll * rows_per_pass));
-    passes = passes < 1 ? 1 : passes > 64 ? 64 : passes;
-    const int rows_per_wg = passes * rows_per_pass;
-    dim3 grid((d.n + rows_per_wg - 1) / rows_per_wg, d.batch * d.Hkv);
-    hipLaunchKernelGGL(vproj_l2_mfma_kernel, grid, dim3(GL_THREADS), 0, s, (const bf16_t *)v, (const bf16_t *)gram, vnorm,
-                       d.H, d.G, d.n, d.vs[0], d.vs[1], d.vs[2], passes);
+    // ranges of rows per head: two workgroups per CU over the whole launch where the context allows it, so that
+    // every workgroup is resident from the start (the heads of a kv group then walk the same rows side by side)
+    const int pairs = d.batch * d.Hkv;
+    const int per_range = 8 * ((pairs + 7) / 8) * d.G;
+    int ranges = 512 / per_range;
+    const int most = (d.n + GR_WAVES * GR_BLOCK_ROWS - 1) / (GR_WAVES * GR_BLOCK_ROWS); // a block per wave at least
+    ranges = ranges > most ? most : ranges;
+    ranges = ranges < 1 ? 1 : ranges;
+    int rows_per_range = (d.n + ranges - 1) / ranges;
+    rows_per_range = (rows_per_range + GR_BLOCK_ROWS - 1) / GR_BLOCK_ROWS * GR_BLOCK_ROWS;
+    hipLaunchKernelGGL(vproj_l2_resident_kernel, dim3((unsigned)(per_range * ranges)), dim3(GR_WAVES * 64), 0, s,
+                       (const bf16_t *)v, (const bf16_t *)gram, vnorm, d.H, d.G, d.n, d.vs[0], d.vs[1], d.vs[2], pairs,
+                       ranges, rows_per_range);
     return hipGetLastError();
 }
 
