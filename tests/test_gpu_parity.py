@@ -82,7 +82,8 @@ def test_batch_and_head_dim_64(P):
     check_full(P, cfg32, t, wo_out_in=False, label="b3 dh64 f32")
 
 
-@pytest.mark.parametrize("case", ["llama_gram", "llama_valu", "qwen_gram", "tiny_f32", "dh64_bf16", "g16_gram", "mha_batch2_gram"])
+@pytest.mark.parametrize("case", ["llama_gram", "llama_valu", "qwen_gram", "tiny_f32", "dh64_bf16", "g16_gram", "mha_batch2_gram",
+                                  "twelve_kv_pairs_gram", "short_context_gram"])
 def test_l2_norm_variant(P, case):
     """L2 distance variant: N = ||v W_O^h||_2.  The bf16 d_h = 128 path goes through the Gram matrix
     (exact for the 2-norm); the oracle evaluates the definition (all d_model products) in float64."""
@@ -100,6 +101,10 @@ def test_l2_norm_variant(P, case):
         cfg = reduced(CONFIGS["llama32k"], 2100, d_model=512, n_q_heads=16, n_kv_heads=1)
     elif case == "mha_batch2_gram":
         cfg = reduced(CONFIGS["llama32k"], 1300, d_model=512, n_q_heads=3, n_kv_heads=3, batch=2)
+    elif case == "twelve_kv_pairs_gram":   # more (batch item, kv head) pairs than XCDs: the pair index wraps
+        cfg = reduced(CONFIGS["llama32k"], 900, d_model=512, n_q_heads=8, n_kv_heads=4, batch=3)
+    elif case == "short_context_gram":     # fewer 64-row blocks than waves in a workgroup
+        cfg = reduced(CONFIGS["llama32k"], 130, d_model=512, n_q_heads=4, n_kv_heads=2, window=16)
     else:
         cfg = reduced(CONFIGS["llama32k"], 700, d_model=256, head_dim=64, n_q_heads=6, n_kv_heads=3, window=5)
     t = make_layer(cfg)
@@ -258,12 +263,15 @@ def test_per_head_budgets_and_special_alphas(P):
     assert res.idx[0, 6].tolist() == list(range(1024))
 
 
-def test_strided_kv_views(P):
-    """K and V living inside a larger [batch, n, Hkv, 2*d_h] buffer (token-major, padded rows)."""
+@pytest.mark.parametrize("norm", [1, 2])
+def test_strided_kv_views(P, norm):
+    """K and V living inside a larger [batch, n, Hkv, 2*d_h] buffer (token-major, padded rows), for both norms
+    (the L2 kernel addresses the V rows through a buffer descriptor of its own)."""
     import torch
-    cfg = reduced(CONFIGS["llama32k"], 640, d_model=256)
+    cfg = reduced(CONFIGS["llama32k"], 640, d_model=256 if norm == 1 else 512)
     t = make_layer(cfg)
-    ref = oracle_pass(cfg, t)
+    ref = O.full_pass(t["q_win"], t["k"], t["v"], t["w_o"], cfg.budget, cfg.alpha, pool_kernel=cfg.pool_kernel,
+                      eps=cfg.eps, norm=norm)
     b, Hkv, n, dh = cfg.batch, cfg.n_kv_heads, cfg.n_ctx, cfg.head_dim
     big_k = torch.zeros((b, n, Hkv, 2 * dh), dtype=torch.bfloat16, device="cuda")
     big_v = torch.zeros_like(big_k)
@@ -271,7 +279,8 @@ def test_strided_kv_views(P):
     big_v[..., dh:] = torch.from_numpy(t["v"]).permute(0, 2, 1, 3).to(torch.bfloat16)
     kview = big_k[..., :dh].permute(0, 2, 1, 3)   # [b, Hkv, n, dh] view
     vview = big_v[..., dh:].permute(0, 2, 1, 3)
-    desc = cfg_desc(P, cfg, flags=P.CKV_WO_OUT_IN, k_stride=tuple(kview.stride()[:3]), v_stride=tuple(vview.stride()[:3]))
+    desc = cfg_desc(P, cfg, flags=P.CKV_WO_OUT_IN, k_stride=tuple(kview.stride()[:3]), v_stride=tuple(vview.stride()[:3]),
+                    norm=P.CKV_NORM_L1 if norm == 1 else P.CKV_NORM_L2)
     dev = to_device(cfg, t, True)
     ws = torch.empty(P.workspace_bytes(desc, cfg.budget), dtype=torch.uint8, device="cuda")
     attn = torch.empty((b, Hkv, n), dtype=torch.float32, device="cuda")
