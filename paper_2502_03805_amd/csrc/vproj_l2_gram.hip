@@ -103,31 +103,35 @@ __global__ __launch_bounds__(256) void gram_finish_kernel(const float *__restric
     }
 }
 
-// N^h_i for one query head and one range of rows, with the head's two Gram matrices resident in LDS.
+// N^h_i for HEADS query heads of a kv group and one range of rows, with the heads' Gram matrices resident in LDS.
 //
-// One 4-wave workgroup per (query head, range of rows), two workgroups per CU.  The head's G_hi | G_lo (64 KiB)
-// are fetched once, at the start; after the one barrier that follows, every wave is on its own: it walks its
-// blocks of GR_RB x 16 rows, requests the next block's V fragments (global -> registers) before it starts on
-// the current one, and reads the Gram fragments it needs from LDS.  No barrier and no Gram traffic in the loop.
-// V is read once per query head; the workgroups of a kv group's heads that work on the same rows are neighbours
-// in launch order on one XCD (workgroup L of a 1-D grid runs on XCD L % 8), so the second to the last reader of
-// a row find it in that XCD's L2.
-constexpr int GR_WAVES = 4;
+// One workgroup of 4 * HEADS waves per (HEADS query heads, range of rows): two 4-wave workgroups per CU with one
+// head each, or one 8-wave workgroup with two.  The heads' G_hi | G_lo (64 KiB each) are fetched once, at the
+// start; after the one barrier that follows, every wave is on its own: it walks its blocks of GR_RB x 16 rows,
+// requests the next block's V fragments (global -> registers) before it starts on the current one, and runs the
+// block through the workgroup's heads, reading the Gram fragments it needs from LDS.  No barrier and no Gram
+// traffic in the loop.  V is read once per workgroup of a kv group; the workgroups that work on the same rows are
+// neighbours in launch order on one XCD (workgroup L of a 1-D grid runs on XCD L % 8), so the later readers of a
+// row find it in that XCD's L2.  Two heads per workgroup halve the V traffic (6 % faster with four heads per
+// group); with an odd number of heads the workgroup that is left with one head would idle half of the time
+// (measured 6 % slower with five), so such groups take one head per workgroup.
 constexpr int GR_RB = 4;
 constexpr int GR_BLOCK_ROWS = GR_RB * 16;
 
-__global__ __launch_bounds__(GR_WAVES * 64, 2) void vproj_l2_resident_kernel(const bf16_t *__restrict__ v,
+template <int HEADS>
+__global__ __launch_bounds__(HEADS * 256, HEADS == 1 ? 2 : 1) void vproj_l2_resident_kernel(const bf16_t *__restrict__ v,
                                                                              const bf16_t *__restrict__ gram,
                                                                              float *__restrict__ vnorm, int H, int G, int n,
                                                                              int64_t vs0, int64_t vs1, int64_t vs2, int pairs,
                                                                              int ranges, int rows_per_range)
 {
-    __shared__ __attribute__((aligned(1024))) char lds[2 * GL_G_BYTES]; // G_hi | G_lo, XOR-swizzled
-    const int Hkv = H / G;
+    constexpr int GR_HEADS = HEADS, GR_WAVES = 4 * HEADS;
+    __shared__ __attribute__((aligned(1024))) char lds[GR_HEADS * 2 * GL_G_BYTES]; // per head: G_hi | G_lo, XOR-swizzled
+    const int Hkv = H / G, hgroups = G / GR_HEADS; // (the launcher takes HEADS = 2 for even G only)
     const int L = blockIdx.x, xcd = L & 7;
     int r = L >> 3;
-    const int hl = r % G;
-    r /= G;
+    const int hl = (r % hgroups) * GR_HEADS;                 // first head of this workgroup inside its kv group
+    r /= hgroups;
     const int range = r % ranges;
     const int pair = (r / ranges) * 8 + xcd;
     if (pair >= pairs) return; // uniform over the workgroup
@@ -141,18 +145,18 @@ __global__ __launch_bounds__(GR_WAVES * 64, 2) void vproj_l2_resident_kernel(con
     const int nblk = (row_end - row_begin + GR_BLOCK_ROWS - 1) / GR_BLOCK_ROWS;
     const bf16_t *vbase = v + bi * vs0 + g * vs1;
 
-    {   // the head's 64 KiB: 64 direct loads of 1 KiB, 16 per wave; row u of a matrix is 256 B = 16 chunks;
+    for (int hh = 0; hh < GR_HEADS; ++hh) {   // a head's 64 KiB: 64 direct loads of 1 KiB; row u of a matrix is 256 B = 16 chunks;
         // chunk q sits at slot q ^ f(u), f(u) = 4 * ((u / 8) % 4) + u % 4: the 16 rows that one MFMA A operand reads
         // together (see below) have 16 different f, so their 16-byte reads fall on different banks
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(gram + (size_t)h * 2 * GL_DH * GL_DH), 0, 2 * GL_G_BYTES, 0x00020000);
+            (void *)(gram + (size_t)(h + hh) * 2 * GL_DH * GL_DH), 0, 2 * GL_G_BYTES, 0x00020000);
 #pragma unroll
         for (int j = 0; j < 64 / GR_WAVES; ++j) {
             const int kib = j * GR_WAVES + wave;
             const int urow = (kib * 4 + (lane >> 4)) & (GL_DH - 1);
             const int f = ((urow >> 3) & 3) * 4 + (urow & 3);
             const uint32_t voff = (uint32_t)(kib * 1024 + (lane >> 4) * 256 + (((lane & 15) ^ f) * 16));
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(lds + kib * 1024), 16, voff, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(lds + hh * 2 * GL_G_BYTES + kib * 1024), 16, voff, 0, 0, 0);
         }
     }
     // V rows through a buffer descriptor over this kv head's rows (the host checks that they span less than 2 GiB, so
@@ -193,6 +197,10 @@ __global__ __launch_bounds__(GR_WAVES * 64, 2) void vproj_l2_resident_kernel(con
         constexpr int CUR = decltype(cur_c)::value;
         load_v_half(blk, 1, vb);
         load_v_half(blk + GR_WAVES, 0, va[CUR ^ 1]); // unconditional (clamped rows): the wait counts stay exact
+        // the block's fragments serve every head of the workgroup, one after the other
+#pragma unroll 1
+        for (int hh = 0; hh < GR_HEADS; ++hh) {
+        const char *gl = lds + hh * 2 * GL_G_BYTES;
         float nsq[GR_RB];
 #pragma unroll
         for (int rb = 0; rb < GR_RB; ++rb) nsq[rb] = 0.f;
@@ -200,7 +208,7 @@ __global__ __launch_bounds__(GR_WAVES * 64, 2) void vproj_l2_resident_kernel(con
         // registers as soon as this ub's MFMAs are issued and arrive under its epilogue and the other wave's work
         bf16x8 gf[8];
         auto read_g = [&](int ub) {
-            const char *rowp = lds + (32 * (ub >> 1) + 4 * (ub & 1) + a_row) * 256;
+            const char *rowp = gl + (32 * (ub >> 1) + 4 * (ub & 1) + a_row) * 256;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 if (s > (ub >> 1)) continue; // (rows of block sp meet the k-chunks s <= sp only)
@@ -247,7 +255,8 @@ __global__ __launch_bounds__(GR_WAVES * 64, 2) void vproj_l2_resident_kernel(con
             x += __shfl_xor(x, 16);
             x += __shfl_xor(x, 32);
             const int row = row0 + rb * 16 + l16;
-            if (kc == 0 && row < row_end) out[row] = sqrtf(fmaxf(x, 0.f));
+            if (kc == 0 && row < row_end) out[(size_t)hh * n + row] = sqrtf(fmaxf(x, 0.f));
+        }
         }
     };
     for (int blk = wave; blk < nblk; blk += 2 * GR_WAVES) {
@@ -281,19 +290,25 @@ hipError_t launch_gram(const Dims &d, const void *w_t, void *gram_out, void *par
 
 hipError_t launch_vproj_l2_mfma(const Dims &d, const void *v, const void *gram, float *vnorm, hipStream_t s)
 {
-    // ranges of rows per head: two workgroups per CU over the whole launch where the context allows it, so that
-    // every workgroup is resident from the start (the heads of a kv group then walk the same rows side by side)
+    // heads per workgroup: two where the group's heads pair up, else one
+    const int heads = d.G % 2 == 0 ? 2 : 1, waves = 4 * heads;
+    // ranges of rows per workgroup of heads: eight waves per CU over the whole launch where the context allows it,
+    // so that every workgroup is resident from the start (a kv group's workgroups then walk the same rows side by side)
     const int pairs = d.batch * d.Hkv;
-    const int per_range = 8 * ((pairs + 7) / 8) * d.G;
-    int ranges = 512 / per_range;
-    const int most = (d.n + GR_WAVES * GR_BLOCK_ROWS - 1) / (GR_WAVES * GR_BLOCK_ROWS); // a block per wave at least
+    const int per_range = 8 * ((pairs + 7) / 8) * (d.G / heads);
+    int ranges = (512 / heads) / per_range;
+    const int most = (d.n + waves * GR_BLOCK_ROWS - 1) / (waves * GR_BLOCK_ROWS); // a block per wave at least
     ranges = ranges > most ? most : ranges;
     ranges = ranges < 1 ? 1 : ranges;
     int rows_per_range = (d.n + ranges - 1) / ranges;
     rows_per_range = (rows_per_range + GR_BLOCK_ROWS - 1) / GR_BLOCK_ROWS * GR_BLOCK_ROWS;
-    hipLaunchKernelGGL(vproj_l2_resident_kernel, dim3((unsigned)(per_range * ranges)), dim3(GR_WAVES * 64), 0, s,
-                       (const bf16_t *)v, (const bf16_t *)gram, vnorm, d.H, d.G, d.n, d.vs[0], d.vs[1], d.vs[2], pairs,
-                       ranges, rows_per_range);
+    const dim3 grid((unsigned)(per_range * ranges)), block(waves * 64);
+    if (heads == 2)
+        hipLaunchKernelGGL(vproj_l2_resident_kernel<2>, grid, block, 0, s, (const bf16_t *)v, (const bf16_t *)gram, vnorm,
+                           d.H, d.G, d.n, d.vs[0], d.vs[1], d.vs[2], pairs, ranges, rows_per_range);
+    else
+        hipLaunchKernelGGL(vproj_l2_resident_kernel<1>, grid, block, 0, s, (const bf16_t *)v, (const bf16_t *)gram, vnorm,
+                           d.H, d.G, d.n, d.vs[0], d.vs[1], d.vs[2], pairs, ranges, rows_per_range);
     return hipGetLastError();
 }
 
