@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # calibration are written up in profiles/whole_pass_llama_hbm_counters.md.  None where not measured.
 VPROJ_TRAFFIC_BYTES = {"llama32k": int(190.0 * 2**20), "llama128k": int(607.1 * 2**20), "qwen128k": int(1751.4 * 2**20)}
 # the same for the Gram-matrix kernel of the L2 variant (95.2 + 4.0 and 383.3 + 16.0 MiB)
-L2_TRAFFIC_BYTES = {"llama32k": int(73.8 * 2**20), "llama128k": int(294.4 * 2**20)}
+L2_TRAFFIC_BYTES = {"llama32k": int(77.2 * 2**20), "llama128k": int(281.8 * 2**20)}
 
 
 class HipEvents:
